@@ -1,0 +1,119 @@
+"""Seeded synthetic inputs shared by the tests, the smoke check and the benchmark.
+
+This module holds no attention arithmetic: it draws numbers, rounds them to the storage
+dtype and draws block masks.  Both the GPU path and the CPU oracle are fed from here.
+
+The generator is counter based (numpy's Philox keyed by seed, workload index and tensor
+index), so a tensor's values do not depend on the order in which tensors are drawn.
+"""
+from dataclasses import dataclass, replace
+
+import numpy as np
+
+BASE_SEED = 241009397
+TENSOR_IDS = {"Q": 0, "K": 1, "V": 2, "dO": 3, "mask": 4}
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    index: int
+    batch: int
+    heads: int
+    n: int
+    d: int
+    dtype: str            # "f32" or "bf16": storage type of Q, K, V, O, dO and the gradients
+    causal: bool = False
+    sparse: bool = False  # block-sparse mask: diagonal block + `extra_blocks` others per row
+    block: int = 128
+    extra_frac: float = 0.10
+    dO_std: float = 1.0
+
+    @property
+    def scale(self):
+        return 1.0 / float(np.sqrt(self.d))
+
+    @property
+    def nblk(self):
+        return (self.n + self.block - 1) // self.block
+
+    @property
+    def extra_blocks(self):
+        """Non-diagonal key blocks kept per query-block row (fixed count, not Bernoulli)."""
+        return int(round(self.extra_frac * (self.nblk - 1))) if self.sparse else 0
+
+    def kept_fraction(self):
+        """Fraction of the n x n score matrix counted as visible when quoting FLOPs
+        (causal is counted as one half; the exact share is (n + 1) / 2n)."""
+        if self.sparse:
+            return (1 + self.extra_blocks) / self.nblk
+        if self.causal:
+            return 0.5
+        return 1.0
+
+    def bwd_flops(self):
+        """Algorithmic backward FLOPs: five n x n x d contractions over visible pairs."""
+        return 10.0 * self.batch * self.heads * self.n * self.n * self.d * self.kept_fraction()
+
+    def fwd_flops(self):
+        return 4.0 * self.batch * self.heads * self.n * self.n * self.d * self.kept_fraction()
+
+    def small(self, **kw):
+        """A reduced copy (same structure, smaller sizes) for oracle-speed parity cases."""
+        return replace(self, **kw)
+
+
+# The five workloads the metric is defined on.
+WORKLOADS = [
+    Workload("cfg1_f32_n256_d64", 1, 1, 1, 256, 64, "f32"),
+    Workload("cfg2_bf16_n2048_d64", 2, 4, 16, 2048, 64, "bf16"),
+    Workload("cfg3_bf16_n8192_d128_causal", 3, 2, 32, 8192, 128, "bf16", causal=True, dO_std=0.1),
+    Workload("cfg4_bf16_n4096_d512_larged", 4, 1, 8, 4096, 512, "bf16"),
+    Workload("cfg5_bf16_n16384_d128_blocksparse", 5, 1, 16, 16384, 128, "bf16", sparse=True),
+]
+
+
+def workload(index):
+    return WORKLOADS[index - 1]
+
+
+def _rng(seed, workload_index, tensor_id):
+    return np.random.Generator(np.random.Philox(key=[(int(seed) << 8) ^ int(workload_index), int(tensor_id)]))
+
+
+def round_to_bf16(x):
+    """float32 -> nearest bfloat16 (ties to even), returned widened back to float32."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    u = (u + (((u >> 16) & 1) + 0x7FFF)) & np.uint32(0xFFFF0000)
+    return u.view(np.float32)
+
+
+def normal(shape, std, seed, workload_index, tensor, dtype):
+    """iid N(0, std^2) as float32, already rounded to the storage dtype."""
+    x = _rng(seed, workload_index, TENSOR_IDS[tensor]).standard_normal(shape, dtype=np.float32)
+    if std != 1.0:
+        x = x * np.float32(std)
+    return round_to_bf16(x) if dtype == "bf16" else x
+
+
+def block_mask(nblk, extra, seed, workload_index):
+    """[nblk, nblk] uint8: the diagonal block plus `extra` distinct other key blocks per
+    query-block row, drawn without replacement, uniformly, from the seeded stream."""
+    rng = _rng(seed, workload_index, TENSOR_IDS["mask"])
+    keep = np.zeros((nblk, nblk), dtype=np.uint8)
+    for i in range(nblk):
+        keep[i, i] = 1
+        others = np.delete(np.arange(nblk), i)
+        if extra > 0:
+            keep[i, rng.choice(others, size=min(extra, nblk - 1), replace=False)] = 1
+    return keep
+
+
+def make_inputs(w, seed=BASE_SEED):
+    """Q, K, V, dO as float32 numpy arrays [batch, heads, n, d] holding storage-dtype values,
+    plus `keep` (None unless the workload is block sparse)."""
+    shape = (w.batch, w.heads, w.n, w.d)
+    out = {t: normal(shape, w.dO_std if t == "dO" else 1.0, seed, w.index, t, w.dtype)
+           for t in ("Q", "K", "V", "dO")}
+    out["keep"] = block_mask(w.nblk, w.extra_blocks, seed, w.index) if w.sparse else None
+    return out
