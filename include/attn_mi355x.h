@@ -1,0 +1,106 @@
+/*
+ * attn_mi355x.h -- C ABI of libattn_mi355x.so: exact softmax attention, forward and backward,
+ * for AMD MI355X (gfx950).
+ *
+ * What is computed (arXiv 2410.09397, "On Fine-Grained I/O Complexity of Attention Backward
+ * Passes"; the paper's S = A_1 X, A_2, h = A_3 Y are the Q, K, V of this interface):
+ *   forward  (Sec. 3.1, forward definition; App. B.4, definitions of A, l, f, O)
+ *       s_ij = scale * <Q_i, K_j> over visible (i, j);  l_i = sum_j exp(s_ij);
+ *       O_i = sum_j exp(s_ij) / l_i * V_j;              LSE_i = log l_i
+ *   backward (App. B.4, definitions of q and p; Sec. 3.1, backward gradient; the tiling follows
+ *             the large-cache phase-2 algorithm of App. D for d <= 128 and the four-phase
+ *             small-cache algorithm of App. C for d > 128)
+ *       f_ij = exp(s_ij - LSE_i);  v_i = <dO_i, O_i>;  q_ij = <dO_i, V_j>;  p_ij = f_ij (q_ij - v_i)
+ *       dV_j = sum_i f_ij dO_i;  dK_j = scale sum_i p_ij Q_i;  dQ_i = scale sum_j p_ij K_j
+ * The paper has no scale and no mask; scale multiplies Q K^T, and a pair (i, j) is visible iff
+ * (!causal || j <= i) and, when a block mask is given, the mask keeps block (i/block, j/block).
+ * A query with no visible key gets O = 0, LSE = -inf and contributes no gradient.
+ *
+ * Conventions
+ *   - Every tensor pointer is DEVICE memory owned by the caller.  Q, K, V, O, dO, dQ, dK, dV are
+ *     [batch, heads, n, d] with element strides (stride_b, stride_h, stride_n, 1), the same for
+ *     all of them; LSE is contiguous [batch, heads, n] float.  Outputs are overwritten.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream);
+ *     calls return without synchronising.  The library allocates no device memory and keeps no
+ *     state between calls; scratch comes from the caller's workspace (attn_workspace_bytes).
+ *   - Arguments are validated on the host before anything is launched; a failed call launches
+ *     nothing and leaves outputs untouched.  batch * heads * n == 0 is a valid empty call.
+ *   - Supported: d a multiple of 8 for ATTN_BF16 (pointers and strides 16-byte aligned), any d
+ *     for ATTN_F32, 1 <= d <= 512.  ATTN_BF16 with d in {64, 128} (block masks: block == 128) runs
+ *     the bf16-MFMA kernels with fp32 accumulation; ATTN_F32 runs fp32 FMA kernels only.
+ */
+#ifndef ATTN_MI355X_H
+#define ATTN_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ATTN_OK = 0,
+    ATTN_ERR_INVALID_ARG = 1, /* null pointer, negative size, misaligned stride, malformed mask */
+    ATTN_ERR_UNSUPPORTED = 2, /* valid request outside the supported set (d, dtype) */
+    ATTN_ERR_WORKSPACE = 3,   /* workspace missing or smaller than attn_workspace_bytes() */
+    ATTN_ERR_DEVICE = 4       /* the HIP runtime reported an error at launch */
+} attn_status;
+
+typedef enum { ATTN_F32 = 0, ATTN_BF16 = 1 } attn_dtype;
+
+typedef struct {
+    int32_t batch, heads, n, d;
+    float scale;    /* multiplies Q K^T; callers usually pass 1/sqrt(d) */
+    int32_t causal; /* 0 or 1: key j visible to query i iff j <= i */
+    int32_t dtype;  /* attn_dtype of Q, K, V, O, dO, dQ, dK, dV */
+    int64_t stride_b, stride_h, stride_n; /* in elements; the d axis has stride 1 */
+} attn_desc;
+
+/*
+ * Block mask shared by all (batch, head) pairs: an nblk x nblk pattern of kept blocks, with
+ * nblk = ceil(n / block), in both compressed orientations (DEVICE int32 arrays, caller owned):
+ *   row_ptr[nblk+1], col_idx[nnz]: key blocks kept for each query-block row, ascending;
+ *   col_ptr[nblk+1], row_idx[nnz]: query blocks kept for each key-block column, ascending.
+ * The two must describe the same set; attn_blockmask_validate checks host copies.
+ */
+typedef struct {
+    int32_t block;
+    int32_t nblk;
+    const int32_t *row_ptr, *col_idx;
+    const int32_t *col_ptr, *row_idx;
+} attn_blockmask;
+
+/* Bytes of device scratch attn_bwd / attn_bwd_blocksparse need for `desc` (0 if desc is
+ * invalid).  attn_fwd needs none. */
+size_t attn_workspace_bytes(const attn_desc *desc, const attn_blockmask *mask /* nullable */);
+
+/* Forward: writes O [batch, heads, n, d] and LSE [batch, heads, n].  `mask` may be NULL. */
+attn_status attn_fwd(const attn_desc *desc, const attn_blockmask *mask, const void *Q,
+                     const void *K, const void *V, void *O, float *LSE, void *stream);
+
+/* Backward without block mask: dQ, dK, dV from Q, K, V, the forward's O and LSE, and dO. */
+attn_status attn_bwd(const attn_desc *desc, const void *Q, const void *K, const void *V,
+                     const void *O, const void *dO, const float *LSE, void *dQ, void *dK,
+                     void *dV, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Backward under a block mask (the sparse setting of Sec. 4.3; the paper gives bounds for it,
+ * no algorithm).  `mask` must not be NULL.  Gradients of fully masked key rows are zero. */
+attn_status attn_bwd_blocksparse(const attn_desc *desc, const attn_blockmask *mask,
+                                 const void *Q, const void *K, const void *V, const void *O,
+                                 const void *dO, const float *LSE, void *dQ, void *dK, void *dV,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+
+/* Checks HOST copies of a block mask: monotone pointers, strictly ascending in-range indices,
+ * nblk == ceil(n / block), and that the two orientations hold the same pairs. */
+attn_status attn_blockmask_validate(int32_t block, int32_t nblk, int32_t n,
+                                    const int32_t *row_ptr, const int32_t *col_idx,
+                                    const int32_t *col_ptr, const int32_t *row_idx);
+
+/* Static description of a status code. */
+const char *attn_status_str(attn_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ATTN_MI355X_H */

@@ -1,0 +1,179 @@
+"""ctypes binding of libattn_mi355x.so: argument marshalling only.
+
+Every function here has the name and meaning of the C entry point it wraps (see
+include/attn_mi355x.h).  PyTorch supplies device memory and the current HIP stream; all
+arithmetic runs in the library's kernels.  There is no CPU fallback: if the shared library
+is missing, loading raises.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libattn_mi355x.so")
+
+ATTN_OK, ATTN_ERR_INVALID_ARG, ATTN_ERR_UNSUPPORTED, ATTN_ERR_WORKSPACE, ATTN_ERR_DEVICE = range(5)
+ATTN_F32, ATTN_BF16 = 0, 1
+
+EXPORTS = ("attn_workspace_bytes", "attn_fwd", "attn_bwd", "attn_bwd_blocksparse",
+           "attn_blockmask_validate", "attn_status_str")
+
+
+class attn_desc(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("heads", ctypes.c_int32), ("n", ctypes.c_int32),
+                ("d", ctypes.c_int32), ("scale", ctypes.c_float), ("causal", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64),
+                ("stride_n", ctypes.c_int64)]
+
+
+class attn_blockmask(ctypes.Structure):
+    _fields_ = [("block", ctypes.c_int32), ("nblk", ctypes.c_int32),
+                ("row_ptr", ctypes.c_void_p), ("col_idx", ctypes.c_void_p),
+                ("col_ptr", ctypes.c_void_p), ("row_idx", ctypes.c_void_p)]
+
+
+class AttnError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s: %s" % (where, status_str(status)))
+
+
+_lib = None
+
+
+def lib():
+    """The loaded shared library (raises OSError if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise OSError("libattn_mi355x.so is not built: run `python -m paper_2410_09397_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, dp, mp = ctypes.c_void_p, ctypes.POINTER(attn_desc), ctypes.POINTER(attn_blockmask)
+        i32p = ctypes.POINTER(ctypes.c_int32)
+        L.attn_workspace_bytes.restype = ctypes.c_size_t
+        L.attn_workspace_bytes.argtypes = [dp, mp]
+        L.attn_fwd.restype = ctypes.c_int
+        L.attn_fwd.argtypes = [dp, mp, vp, vp, vp, vp, vp, vp]
+        L.attn_bwd.restype = ctypes.c_int
+        L.attn_bwd.argtypes = [dp] + [vp] * 9 + [vp, ctypes.c_size_t, vp]
+        L.attn_bwd_blocksparse.restype = ctypes.c_int
+        L.attn_bwd_blocksparse.argtypes = [dp, mp] + [vp] * 9 + [vp, ctypes.c_size_t, vp]
+        L.attn_blockmask_validate.restype = ctypes.c_int
+        L.attn_blockmask_validate.argtypes = [ctypes.c_int32] * 3 + [i32p] * 4
+        L.attn_status_str.restype = ctypes.c_char_p
+        L.attn_status_str.argtypes = [ctypes.c_int]
+        _lib = L
+    return _lib
+
+
+def status_str(status):
+    return lib().attn_status_str(int(status)).decode()
+
+
+def csr_csc_from_dense(keep):
+    """Host int32 arrays (row_ptr, col_idx, col_ptr, row_idx) of an [nblk, nblk] 0/1 matrix."""
+    keep = np.asarray(keep) != 0
+    nblk = keep.shape[0]
+    row_ptr = np.zeros(nblk + 1, np.int32)
+    row_ptr[1:] = np.cumsum(keep.sum(1))
+    col_idx = np.nonzero(keep)[1].astype(np.int32)
+    col_ptr = np.zeros(nblk + 1, np.int32)
+    col_ptr[1:] = np.cumsum(keep.sum(0))
+    row_idx = np.nonzero(keep.T)[1].astype(np.int32)
+    return row_ptr, col_idx, col_ptr, row_idx
+
+
+def attn_blockmask_validate(block, nblk, n, row_ptr, col_idx, col_ptr, row_idx):
+    """Status code of the host-side structural check of a block mask (numpy int32 arrays)."""
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    arrs = [np.ascontiguousarray(a, dtype=np.int32) if a is not None else None
+            for a in (row_ptr, col_idx, col_ptr, row_idx)]
+    ptrs = [a.ctypes.data_as(i32p) if a is not None else None for a in arrs]
+    return lib().attn_blockmask_validate(int(block), int(nblk), int(n), *ptrs)
+
+
+class BlockMask:
+    """Device copies of a block mask in both compressed orientations."""
+
+    def __init__(self, keep, block, n, device="cuda"):
+        import torch
+        self.block, self.n = int(block), int(n)
+        self.nblk = int(np.asarray(keep).shape[0])
+        self.host = csr_csc_from_dense(keep)
+        st = attn_blockmask_validate(self.block, self.nblk, self.n, *self.host)
+        if st != ATTN_OK:
+            raise AttnError(st, "attn_blockmask_validate")
+        self.dev = [torch.from_numpy(a).to(device) for a in self.host]
+        self.c = attn_blockmask(self.block, self.nblk, *[t.data_ptr() for t in self.dev])
+
+
+def _desc(x, scale, causal):
+    import torch
+    if x.dim() != 4 or x.stride(3) != 1:
+        raise ValueError("expected a [batch, heads, n, d] tensor with unit stride along d")
+    dt = {torch.float32: ATTN_F32, torch.bfloat16: ATTN_BF16}[x.dtype]
+    b, h, n, d = x.shape
+    return attn_desc(b, h, n, d, float(scale), int(bool(causal)), dt, x.stride(0), x.stride(1), x.stride(2))
+
+
+def _same_layout(ref, *others):
+    for t in others:
+        if t.shape != ref.shape or t.stride() != ref.stride() or t.dtype != ref.dtype or t.device != ref.device:
+            raise ValueError("all [batch, heads, n, d] tensors must share shape, strides, dtype and device")
+
+
+def _stream(stream):
+    import torch
+    return (stream if stream is not None else torch.cuda.current_stream()).cuda_stream
+
+
+def attn_workspace_bytes(desc, mask=None):
+    return lib().attn_workspace_bytes(ctypes.byref(desc), ctypes.byref(mask.c) if mask is not None else None)
+
+
+def attn_fwd(Q, K, V, scale, causal=False, mask=None, stream=None, out=None):
+    """O, LSE = forward(Q, K, V) on the GPU.  Q, K, V: cuda tensors [batch, heads, n, d]."""
+    import torch
+    _same_layout(Q, K, V)
+    desc = _desc(Q, scale, causal)
+    O = out[0] if out is not None else torch.empty_like(Q)
+    LSE = out[1] if out is not None else torch.empty(Q.shape[:3], dtype=torch.float32, device=Q.device)
+    _same_layout(Q, O)
+    st = lib().attn_fwd(ctypes.byref(desc), ctypes.byref(mask.c) if mask is not None else None,
+                        Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), LSE.data_ptr(), _stream(stream))
+    if st != ATTN_OK:
+        raise AttnError(st, "attn_fwd")
+    return O, LSE
+
+
+def _bwd(name, Q, K, V, O, dO, LSE, scale, causal, mask, stream, out, workspace):
+    import torch
+    _same_layout(Q, K, V, O, dO)
+    desc = _desc(Q, scale, causal)
+    dQ, dK, dV = out if out is not None else (torch.empty_like(Q), torch.empty_like(Q), torch.empty_like(Q))
+    _same_layout(Q, dQ, dK, dV)
+    if LSE.dtype != torch.float32 or not LSE.is_contiguous() or LSE.shape != Q.shape[:3]:
+        raise ValueError("LSE must be a contiguous float32 [batch, heads, n] tensor")
+    need = attn_workspace_bytes(desc, mask)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=Q.device)
+    args = [Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), dO.data_ptr(), LSE.data_ptr(),
+            dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream(stream)]
+    if name == "attn_bwd":
+        st = lib().attn_bwd(ctypes.byref(desc), *args)
+    else:
+        st = lib().attn_bwd_blocksparse(ctypes.byref(desc), ctypes.byref(mask.c), *args)
+    if st != ATTN_OK:
+        raise AttnError(st, name)
+    return dQ, dK, dV
+
+
+def attn_bwd(Q, K, V, O, dO, LSE, scale, causal=False, stream=None, out=None, workspace=None):
+    """dQ, dK, dV from the forward's O and LSE (no block mask)."""
+    return _bwd("attn_bwd", Q, K, V, O, dO, LSE, scale, causal, None, stream, out, workspace)
+
+
+def attn_bwd_blocksparse(Q, K, V, O, dO, LSE, scale, mask, causal=False, stream=None, out=None, workspace=None):
+    """dQ, dK, dV under a BlockMask."""
+    return _bwd("attn_bwd_blocksparse", Q, K, V, O, dO, LSE, scale, causal, mask, stream, out, workspace)

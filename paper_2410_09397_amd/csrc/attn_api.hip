@@ -1,0 +1,244 @@
+// C ABI of libattn_mi355x.so: host-side validation and dispatch.  No device memory is
+// allocated here and nothing is launched before every argument has been checked.
+#include <cmath>
+#include <cstring>
+#include <vector>
+
+#include "../../include/attn_mi355x.h"
+#include "attn_internal.hpp"
+
+namespace {
+
+using attn::FusedParams;
+using attn::GenericParams;
+
+enum class Path { kFused, kLargeD, kGeneric };
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+attn_status check_desc(const attn_desc* d) {
+    if (!d) return ATTN_ERR_INVALID_ARG;
+    if (d->batch < 0 || d->heads < 0 || d->n < 0 || d->d < 1) return ATTN_ERR_INVALID_ARG;
+    if (d->causal != 0 && d->causal != 1) return ATTN_ERR_INVALID_ARG;
+    if (!std::isfinite(d->scale)) return ATTN_ERR_INVALID_ARG;
+    if (d->dtype != ATTN_F32 && d->dtype != ATTN_BF16) return ATTN_ERR_UNSUPPORTED;
+    if (d->d > 512) return ATTN_ERR_UNSUPPORTED;
+    if (d->dtype == ATTN_BF16 && d->d % 8 != 0) return ATTN_ERR_UNSUPPORTED;
+    if (d->stride_n < d->d || d->stride_h < 0 || d->stride_b < 0) return ATTN_ERR_INVALID_ARG;
+    if (d->dtype == ATTN_BF16 && (d->stride_n % 8 || d->stride_h % 8 || d->stride_b % 8))
+        return ATTN_ERR_INVALID_ARG;
+    return ATTN_OK;
+}
+
+attn_status check_mask(const attn_desc* d, const attn_blockmask* m) {
+    if (!m) return ATTN_OK;
+    if (m->block < 1 || m->nblk < 0) return ATTN_ERR_INVALID_ARG;
+    if ((long)m->nblk != ((long)d->n + m->block - 1) / m->block) return ATTN_ERR_INVALID_ARG;
+    if (!m->row_ptr || !m->col_idx || !m->col_ptr || !m->row_idx) return ATTN_ERR_INVALID_ARG;
+    return ATTN_OK;
+}
+
+bool is_empty(const attn_desc* d) { return (long)d->batch * d->heads * d->n == 0; }
+
+Path pick_path(const attn_desc* d, const attn_blockmask* m) {
+    if (d->dtype == ATTN_BF16 && (d->d == 64 || d->d == 128) && (!m || m->block == 128)) return Path::kFused;
+    return Path::kGeneric;
+}
+
+size_t delta_bytes(const attn_desc* d) { return round_up((size_t)d->batch * d->heads * d->n * sizeof(float), 256); }
+
+FusedParams fused_params(const attn_desc* d) {
+    FusedParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.stride_b = d->stride_b;
+    p.stride_h = d->stride_h;
+    p.stride_n = d->stride_n;
+    p.batch = d->batch;
+    p.heads = d->heads;
+    p.n = d->n;
+    p.scale = d->scale;
+    p.causal = d->causal;
+    return p;
+}
+
+GenericParams generic_params(const attn_desc* d, const attn_blockmask* m) {
+    GenericParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.stride_b = d->stride_b;
+    p.stride_h = d->stride_h;
+    p.stride_n = d->stride_n;
+    p.batch = d->batch;
+    p.heads = d->heads;
+    p.n = d->n;
+    p.d = d->d;
+    p.scale = d->scale;
+    p.causal = d->causal;
+    p.block = 1;
+    if (m) {
+        p.csr_ptr = m->row_ptr;
+        p.csr_idx = m->col_idx;
+        p.csc_ptr = m->col_ptr;
+        p.csc_idx = m->row_idx;
+        p.block = m->block;
+    }
+    return p;
+}
+
+attn_status bwd_impl(const attn_desc* desc, const attn_blockmask* mask, const void* Q, const void* K,
+                     const void* V, const void* O, const void* dO, const float* LSE, void* dQ, void* dK,
+                     void* dV, void* workspace, size_t workspace_bytes, void* stream) {
+    attn_status st = check_desc(desc);
+    if (st != ATTN_OK) return st;
+    st = check_mask(desc, mask);
+    if (st != ATTN_OK) return st;
+    if (is_empty(desc)) return ATTN_OK;
+    if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV) return ATTN_ERR_INVALID_ARG;
+    if (desc->dtype == ATTN_BF16 && !(aligned16(Q) && aligned16(K) && aligned16(V) && aligned16(O) &&
+                                      aligned16(dO) && aligned16(dQ) && aligned16(dK) && aligned16(dV)))
+        return ATTN_ERR_INVALID_ARG;
+    const size_t need = attn_workspace_bytes(desc, mask);
+    if (!workspace || workspace_bytes < need || !aligned16(workspace)) return ATTN_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    switch (pick_path(desc, mask)) {
+        case Path::kFused: {
+            FusedParams p = fused_params(desc);
+            p.Q = static_cast<const __bf16*>(Q);
+            p.K = static_cast<const __bf16*>(K);
+            p.V = static_cast<const __bf16*>(V);
+            p.O = static_cast<const __bf16*>(O);
+            p.dO = static_cast<const __bf16*>(dO);
+            p.dQ = static_cast<__bf16*>(dQ);
+            p.dK = static_cast<__bf16*>(dK);
+            p.dV = static_cast<__bf16*>(dV);
+            p.LSE = LSE;
+            p.delta = static_cast<float*>(workspace);
+            e = attn::launch_bwd_fused(desc->d, p, mask ? mask->row_ptr : nullptr, mask ? mask->col_idx : nullptr,
+                                       mask ? mask->col_ptr : nullptr, mask ? mask->row_idx : nullptr, s);
+            break;
+        }
+        default: {
+            GenericParams p = generic_params(desc, mask);
+            p.Q = Q;
+            p.K = K;
+            p.V = V;
+            p.O_in = O;
+            p.dO = dO;
+            p.dQ = dQ;
+            p.dK = dK;
+            p.dV = dV;
+            p.LSE_in = LSE;
+            p.delta = static_cast<float*>(workspace);
+            e = attn::launch_generic(desc->dtype == ATTN_BF16, true, p, s);
+            break;
+        }
+    }
+    return e == hipSuccess ? ATTN_OK : ATTN_ERR_DEVICE;
+}
+
+}  // namespace
+
+#pragma GCC visibility push(default)
+extern "C" {
+
+size_t attn_workspace_bytes(const attn_desc* desc, const attn_blockmask* mask) {
+    if (check_desc(desc) != ATTN_OK || check_mask(desc, mask) != ATTN_OK) return 0;
+    if (is_empty(desc)) return 256;
+    return delta_bytes(desc);
+}
+
+attn_status attn_fwd(const attn_desc* desc, const attn_blockmask* mask, const void* Q, const void* K,
+                     const void* V, void* O, float* LSE, void* stream) {
+    attn_status st = check_desc(desc);
+    if (st != ATTN_OK) return st;
+    st = check_mask(desc, mask);
+    if (st != ATTN_OK) return st;
+    if (is_empty(desc)) return ATTN_OK;
+    if (!Q || !K || !V || !O || !LSE) return ATTN_ERR_INVALID_ARG;
+    if (desc->dtype == ATTN_BF16 && !(aligned16(Q) && aligned16(K) && aligned16(V) && aligned16(O)))
+        return ATTN_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    switch (pick_path(desc, mask)) {
+        case Path::kFused: {
+            FusedParams p = fused_params(desc);
+            p.Q = static_cast<const __bf16*>(Q);
+            p.K = static_cast<const __bf16*>(K);
+            p.V = static_cast<const __bf16*>(V);
+            p.Oout = static_cast<__bf16*>(O);
+            p.LSEout = LSE;
+            e = attn::launch_fwd_fused(desc->d, p, mask ? mask->row_ptr : nullptr, mask ? mask->col_idx : nullptr, s);
+            break;
+        }
+        default: {
+            GenericParams p = generic_params(desc, mask);
+            p.Q = Q;
+            p.K = K;
+            p.V = V;
+            p.O = O;
+            p.LSE_out = LSE;
+            e = attn::launch_generic(desc->dtype == ATTN_BF16, false, p, s);
+            break;
+        }
+    }
+    return e == hipSuccess ? ATTN_OK : ATTN_ERR_DEVICE;
+}
+
+attn_status attn_bwd(const attn_desc* desc, const void* Q, const void* K, const void* V, const void* O,
+                     const void* dO, const float* LSE, void* dQ, void* dK, void* dV, void* workspace,
+                     size_t workspace_bytes, void* stream) {
+    return bwd_impl(desc, nullptr, Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, stream);
+}
+
+attn_status attn_bwd_blocksparse(const attn_desc* desc, const attn_blockmask* mask, const void* Q,
+                                 const void* K, const void* V, const void* O, const void* dO, const float* LSE,
+                                 void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes,
+                                 void* stream) {
+    if (!mask) return ATTN_ERR_INVALID_ARG;
+    return bwd_impl(desc, mask, Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, stream);
+}
+
+attn_status attn_blockmask_validate(int32_t block, int32_t nblk, int32_t n, const int32_t* row_ptr,
+                                    const int32_t* col_idx, const int32_t* col_ptr, const int32_t* row_idx) {
+    if (block < 1 || nblk < 0 || n < 0) return ATTN_ERR_INVALID_ARG;
+    if ((long)nblk != ((long)n + block - 1) / block) return ATTN_ERR_INVALID_ARG;
+    if (!row_ptr || !col_ptr || (nblk > 0 && (!col_idx || !row_idx))) return ATTN_ERR_INVALID_ARG;
+    if (row_ptr[0] != 0 || col_ptr[0] != 0) return ATTN_ERR_INVALID_ARG;
+    for (int a = 0; a < nblk; ++a) {
+        if (row_ptr[a + 1] < row_ptr[a] || col_ptr[a + 1] < col_ptr[a]) return ATTN_ERR_INVALID_ARG;
+        if (row_ptr[a + 1] - row_ptr[a] > nblk || col_ptr[a + 1] - col_ptr[a] > nblk) return ATTN_ERR_INVALID_ARG;
+    }
+    if (row_ptr[nblk] != col_ptr[nblk]) return ATTN_ERR_INVALID_ARG;
+    std::vector<unsigned char> keep((size_t)nblk * nblk, 0);
+    for (int i = 0; i < nblk; ++i)
+        for (int a = row_ptr[i]; a < row_ptr[i + 1]; ++a) {
+            const int j = col_idx[a];
+            if (j < 0 || j >= nblk) return ATTN_ERR_INVALID_ARG;
+            if (a > row_ptr[i] && col_idx[a - 1] >= j) return ATTN_ERR_INVALID_ARG;
+            keep[(size_t)i * nblk + j] = 1;
+        }
+    for (int j = 0; j < nblk; ++j)
+        for (int a = col_ptr[j]; a < col_ptr[j + 1]; ++a) {
+            const int i = row_idx[a];
+            if (i < 0 || i >= nblk) return ATTN_ERR_INVALID_ARG;
+            if (a > col_ptr[j] && row_idx[a - 1] >= i) return ATTN_ERR_INVALID_ARG;
+            if (!keep[(size_t)i * nblk + j]) return ATTN_ERR_INVALID_ARG;
+        }
+    return ATTN_OK;
+}
+
+const char* attn_status_str(attn_status s) {
+    switch (s) {
+        case ATTN_OK: return "ok";
+        case ATTN_ERR_INVALID_ARG: return "invalid argument";
+        case ATTN_ERR_UNSUPPORTED: return "unsupported configuration";
+        case ATTN_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case ATTN_ERR_DEVICE: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"
+#pragma GCC visibility pop

@@ -1,0 +1,398 @@
+// Fused backward kernels for d <= 128 (the regime where a d x d working set fits on chip):
+//   delta   = rowsum(dO o O)                                  (second matrix form of p, App. B.4)
+//   dK, dV  : one workgroup owns a block of 128 keys and streams query tiles
+//   dQ      : one workgroup owns a block of 128 queries and streams key tiles
+// Per tile pair this is the inner body of the paper's large-cache phase-2 algorithm (App. D):
+// q = dO h^T, A = S A_2^T, f = exp(A) / l, p = f o q - diag(v) f, followed by the three
+// products that use f and p.  The resident operand is the owned block, so dK/dV (resp. dQ)
+// accumulate in registers with no atomics and no n x n matrix ever leaves the chip.
+#include "attn_common.hpp"
+#include "attn_internal.hpp"
+
+namespace attn {
+
+// --------------------------------------------------------------------------------- delta
+// One wavefront per row; lanes read 16-byte chunks and the row sum is a shuffle reduction.
+template <int D>
+__global__ void __launch_bounds__(kThreads) delta_kernel(FusedParams p) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const long rows = (long)p.batch * p.heads * p.n;
+    const long r = (long)blockIdx.x * 4 + w;
+    if (r >= rows) return;
+    const int bh = (int)(r / p.n), i = (int)(r % p.n);
+    const long base = (long)(bh / p.heads) * p.stride_b + (long)(bh % p.heads) * p.stride_h + (long)i * p.stride_n;
+    float acc = 0.f;
+    for (int c = lane; c < D / 8; c += 64) {
+        bf16x8 o = *reinterpret_cast<const bf16x8*>(p.O + base + c * 8);
+        bf16x8 g = *reinterpret_cast<const bf16x8*>(p.dO + base + c * 8);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) acc += (float)o[t] * (float)g[t];
+    }
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
+    if (lane == 0) p.delta[r] = acc;
+}
+
+// ------------------------------------------------------------------------------- dK, dV
+// Wave w owns keys j0 + 32w .. +31: their K and V rows stay in registers as B operands.
+// Per query tile (64 rows, two 32-row halves T):
+//   S[T]  = Q_T K_w^T, dP[T] = dO_T V_w^T           accumulator: lane <-> key, register <-> query
+//   P = exp2(c S - lse2), dS = P (dP - delta)        in registers, then packed to bf16
+//   dV_w^T += dO_T^T P,   dK_w^T += Q_T^T dS         accumulators are B operands as they stand;
+//                                                    Q^T / dO^T come from transposed LDS reads
+template <int D>
+__global__ void __launch_bounds__(kThreads, 1) bwd_dkdv_kernel(FusedParams p) {
+    constexpr int BR = 64, BC = 128, KS = D / 16, MT = D / 32;
+    constexpr int kTileBytes = BR * D * 2;
+    constexpr int kStageBytes = 2 * kTileBytes + 2 * BR * 4;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, h = lane >> 5, l32 = lane & 31;
+    const int key_blocks = (p.n + BC - 1) / BC;
+    int bh, j;
+    decode_block(blockIdx.x, key_blocks, p.batch * p.heads, bh, j);
+    const long base = (long)(bh / p.heads) * p.stride_b + (long)(bh % p.heads) * p.stride_h;
+    const long ld = p.stride_n;
+    const int j0 = j * BC;
+    const float* lse_g = p.LSE + (long)bh * p.n;
+    const float* delta_g = p.delta + (long)bh * p.n;
+
+    // iteration space over 64-row query tiles
+    int n_it, t0 = 0, lp0 = 0;
+    if (p.list_ptr) {
+        lp0 = p.list_ptr[j];
+        n_it = (p.list_ptr[j + 1] - lp0) * (128 / BR);
+    } else {
+        t0 = p.causal ? j0 / BR : 0;
+        n_it = (p.n + BR - 1) / BR - t0;
+    }
+    auto tile_start = [&](int it) -> int {
+        if (p.list_ptr) return p.list_idx[lp0 + it / (128 / BR)] * 128 + (it % (128 / BR)) * BR;
+        return (t0 + it) * BR;
+    };
+
+    // resident K, V fragments
+    const int key = j0 + 32 * w + l32;
+    bf16x8 kf[KS], vf[KS];
+    {
+        const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            kf[ks] = zero;
+            vf[ks] = zero;
+            if (key < p.n) {
+                kf[ks] = *reinterpret_cast<const bf16x8*>(p.K + base + (long)key * ld + 16 * ks + 8 * h);
+                vf[ks] = *reinterpret_cast<const bf16x8*>(p.V + base + (long)key * ld + 16 * ks + 8 * h);
+            }
+        }
+    }
+
+    f32x16 dk[MT], dv[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { dk[mt][i] = 0.f; dv[mt][i] = 0.f; }
+
+    const float c = p.scale * kLog2e;
+    TileCopy<D, BR> cq, cdo;
+    float row_stat = 0.f;  // threads 0..63 stage lse2, 64..127 stage delta
+
+    auto fetch = [&](int i0) {
+        cq.fetch(p.Q + base, ld, i0, p.n, tid);
+        cdo.fetch(p.dO + base, ld, i0, p.n, tid);
+        if (tid < BR) {
+            const int q = i0 + tid;
+            row_stat = q < p.n ? lse_g[q] * kLog2e : __builtin_inff();
+        } else if (tid < 2 * BR) {
+            const int q = i0 + tid - BR;
+            row_stat = q < p.n ? delta_g[q] : 0.f;
+        }
+    };
+    auto commit = [&](int stage) {
+        char* s = smem + stage * kStageBytes;
+        cq.store(s, tid);
+        cdo.store(s + kTileBytes, tid);
+        if (tid < 2 * BR) reinterpret_cast<float*>(s + 2 * kTileBytes)[tid] = row_stat;
+    };
+
+    if (n_it > 0) {
+        fetch(tile_start(0));
+        commit(0);
+    }
+    __syncthreads();
+
+    for (int it = 0; it < n_it; ++it) {
+        const int i0 = tile_start(it);
+        const bool more = it + 1 < n_it;
+        if (more) fetch(tile_start(it + 1));
+
+        const char* qs = smem + (it & 1) * kStageBytes;
+        const char* dos = qs + kTileBytes;
+        const float* lse_s = reinterpret_cast<const float*>(qs + 2 * kTileBytes);
+        const float* delta_s = lse_s + BR;
+
+        // causal: a tile whose last query precedes this block's first key sees nothing
+        const bool skip = p.causal && (i0 + BR - 1 < j0);
+        if (!skip) {
+            f32x16 s[2], dp[2];
+#pragma unroll
+            for (int T = 0; T < 2; ++T)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) { s[T][i] = 0.f; dp[T][i] = 0.f; }
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int T = 0; T < 2; ++T) s[T] = mfma32(load_frag<D>(qs, 32 * T, ks, lane), kf[ks], s[T]);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int T = 0; T < 2; ++T) dp[T] = mfma32(load_frag<D>(dos, 32 * T, ks, lane), vf[ks], dp[T]);
+
+            const bool need_mask = p.causal && (i0 < j0 + BC - 1);
+#pragma unroll
+            for (int T = 0; T < 2; ++T)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const f32x4 L = *reinterpret_cast<const f32x4*>(lse_s + 32 * T + 8 * g + 4 * h);
+                    const f32x4 Dl = *reinterpret_cast<const f32x4*>(delta_s + 32 * T + 8 * g + 4 * h);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int i = 4 * g + r;
+                        float pv = __builtin_amdgcn_exp2f(s[T][i] * c - L[r]);
+                        if (need_mask && key > i0 + 32 * T + 8 * g + 4 * h + r) pv = 0.f;
+                        s[T][i] = pv;
+                        dp[T][i] = pv * (dp[T][i] - Dl[r]);
+                    }
+                }
+            bf16x8 pb[2][2], dsb[2][2];
+#pragma unroll
+            for (int T = 0; T < 2; ++T)
+#pragma unroll
+                for (int ss = 0; ss < 2; ++ss) {
+                    pb[T][ss] = acc_to_operand(s[T], ss);
+                    dsb[T][ss] = acc_to_operand(dp[T], ss);
+                }
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int T = 0; T < 2; ++T)
+#pragma unroll
+                    for (int ss = 0; ss < 2; ++ss)
+                        dv[mt] = mfma32(load_frag_t<D>(dos, 32 * mt, 32 * T + 16 * ss, lane), pb[T][ss], dv[mt]);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int T = 0; T < 2; ++T)
+#pragma unroll
+                    for (int ss = 0; ss < 2; ++ss)
+                        dk[mt] = mfma32(load_frag_t<D>(qs, 32 * mt, 32 * T + 16 * ss, lane), dsb[T][ss], dk[mt]);
+        }
+        if (more) commit((it + 1) & 1);
+        __syncthreads();
+    }
+
+    // epilogue: accumulators hold dK^T, dV^T (register <-> d, lane <-> key)
+    if (key < p.n) {
+        __bf16* dk_row = p.dK + base + (long)key * ld;
+        __bf16* dv_row = p.dV + base + (long)key * ld;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int col = 32 * mt + 8 * g + 4 * h;
+                u32x2 a, b;
+                a[0] = pack_bf16(dk[mt][4 * g + 0] * p.scale, dk[mt][4 * g + 1] * p.scale);
+                a[1] = pack_bf16(dk[mt][4 * g + 2] * p.scale, dk[mt][4 * g + 3] * p.scale);
+                b[0] = pack_bf16(dv[mt][4 * g + 0], dv[mt][4 * g + 1]);
+                b[1] = pack_bf16(dv[mt][4 * g + 2], dv[mt][4 * g + 3]);
+                *reinterpret_cast<u32x2*>(dk_row + col) = a;
+                *reinterpret_cast<u32x2*>(dv_row + col) = b;
+            }
+    }
+}
+
+// ----------------------------------------------------------------------------------- dQ
+// Wave w owns queries i0 + 32w .. +31: their Q and dO rows stay in registers as B operands.
+// Per key tile (64 keys, two halves T):
+//   S^T[T] = K_T Q_w^T, dP^T[T] = V_T dO_w^T        accumulator: lane <-> query, register <-> key
+//   dS^T = P^T (dP^T - delta)                        per-lane scalars lse2, delta
+//   dQ_w^T += K_T^T dS^T                             K^T from transposed LDS reads
+template <int D>
+__global__ void __launch_bounds__(kThreads, 1) bwd_dq_kernel(FusedParams p) {
+    constexpr int BR = 128, BC = 64, KS = D / 16, MT = D / 32;
+    constexpr int kTileBytes = BC * D * 2;
+    constexpr int kStageBytes = 2 * kTileBytes;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, h = lane >> 5, l32 = lane & 31;
+    const int q_blocks = (p.n + BR - 1) / BR;
+    int bh, blk;
+    decode_block(blockIdx.x, q_blocks, p.batch * p.heads, bh, blk);
+    const int ib = p.causal ? q_blocks - 1 - blk : blk;  // causal: longest rows first
+    const long base = (long)(bh / p.heads) * p.stride_b + (long)(bh % p.heads) * p.stride_h;
+    const long ld = p.stride_n;
+    const int i0 = ib * BR;
+
+    int n_it, lp0 = 0;
+    if (p.list_ptr) {
+        lp0 = p.list_ptr[ib];
+        n_it = (p.list_ptr[ib + 1] - lp0) * (128 / BC);
+    } else {
+        const int k_end = p.causal ? min(p.n, i0 + BR) : p.n;
+        n_it = (k_end + BC - 1) / BC;
+    }
+    auto tile_start = [&](int it) -> int {
+        if (p.list_ptr) return p.list_idx[lp0 + it / (128 / BC)] * 128 + (it % (128 / BC)) * BC;
+        return it * BC;
+    };
+
+    const int q = i0 + 32 * w + l32;
+    const bool q_ok = q < p.n;
+    bf16x8 qf[KS], gf[KS];
+    {
+        const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            qf[ks] = zero;
+            gf[ks] = zero;
+            if (q_ok) {
+                qf[ks] = *reinterpret_cast<const bf16x8*>(p.Q + base + (long)q * ld + 16 * ks + 8 * h);
+                gf[ks] = *reinterpret_cast<const bf16x8*>(p.dO + base + (long)q * ld + 16 * ks + 8 * h);
+            }
+        }
+    }
+    const float lse2 = q_ok ? p.LSE[(long)bh * p.n + q] * kLog2e : __builtin_inff();
+    const float dl = q_ok ? p.delta[(long)bh * p.n + q] : 0.f;
+
+    f32x16 dq[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) dq[mt][i] = 0.f;
+
+    const float c = p.scale * kLog2e;
+    TileCopy<D, BC> ck, cv;
+    auto fetch = [&](int j0) {
+        ck.fetch(p.K + base, ld, j0, p.n, tid);
+        cv.fetch(p.V + base, ld, j0, p.n, tid);
+    };
+    auto commit = [&](int stage) {
+        char* s = smem + stage * kStageBytes;
+        ck.store(s, tid);
+        cv.store(s + kTileBytes, tid);
+    };
+    if (n_it > 0) {
+        fetch(tile_start(0));
+        commit(0);
+    }
+    __syncthreads();
+
+    for (int it = 0; it < n_it; ++it) {
+        const int j0 = tile_start(it);
+        const bool more = it + 1 < n_it;
+        if (more) fetch(tile_start(it + 1));
+        const char* ks_t = smem + (it & 1) * kStageBytes;
+        const char* vs_t = ks_t + kTileBytes;
+
+        // causal: this wave's last query precedes the tile's first key -> nothing visible
+        const bool skip = p.causal && (i0 + 32 * w + 31 < j0);
+        if (!skip) {
+            f32x16 st[2], dpt[2];
+#pragma unroll
+            for (int T = 0; T < 2; ++T)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) { st[T][i] = 0.f; dpt[T][i] = 0.f; }
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int T = 0; T < 2; ++T) st[T] = mfma32(load_frag<D>(ks_t, 32 * T, ks, lane), qf[ks], st[T]);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int T = 0; T < 2; ++T) dpt[T] = mfma32(load_frag<D>(vs_t, 32 * T, ks, lane), gf[ks], dpt[T]);
+
+            const bool need_mask = (p.causal && (j0 + BC - 1 > i0 + 32 * w)) || (j0 + BC > p.n);
+#pragma unroll
+            for (int T = 0; T < 2; ++T)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    float pv = __builtin_amdgcn_exp2f(st[T][i] * c - lse2);
+                    if (need_mask) {
+                        const int key = j0 + 32 * T + acc_row(i, h);
+                        if (key >= p.n || (p.causal && key > q)) pv = 0.f;
+                    }
+                    dpt[T][i] = pv * (dpt[T][i] - dl);
+                }
+            bf16x8 dsb[2][2];
+#pragma unroll
+            for (int T = 0; T < 2; ++T)
+#pragma unroll
+                for (int ss = 0; ss < 2; ++ss) dsb[T][ss] = acc_to_operand(dpt[T], ss);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int T = 0; T < 2; ++T)
+#pragma unroll
+                    for (int ss = 0; ss < 2; ++ss)
+                        dq[mt] = mfma32(load_frag_t<D>(ks_t, 32 * mt, 32 * T + 16 * ss, lane), dsb[T][ss], dq[mt]);
+        }
+        if (more) commit((it + 1) & 1);
+        __syncthreads();
+    }
+
+    if (q_ok) {
+        __bf16* row = p.dQ + base + (long)q * ld;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                u32x2 a;
+                a[0] = pack_bf16(dq[mt][4 * g + 0] * p.scale, dq[mt][4 * g + 1] * p.scale);
+                a[1] = pack_bf16(dq[mt][4 * g + 2] * p.scale, dq[mt][4 * g + 3] * p.scale);
+                *reinterpret_cast<u32x2*>(row + 32 * mt + 8 * g + 4 * h) = a;
+            }
+    }
+}
+
+// ------------------------------------------------------------------------------ launchers
+template <int D>
+static hipError_t launch_bwd(const FusedParams& p, const int32_t* csr_ptr, const int32_t* csr_idx,
+                             const int32_t* csc_ptr, const int32_t* csc_idx, hipStream_t stream) {
+    const int bh = p.batch * p.heads;
+    const long rows = (long)bh * p.n;
+    hipLaunchKernelGGL(delta_kernel<D>, dim3((unsigned)((rows + 3) / 4)), dim3(kThreads), 0, stream, p);
+
+    constexpr int kv_lds = 2 * (2 * 64 * D * 2 + 2 * 64 * 4);
+    constexpr int q_lds = 2 * (2 * 64 * D * 2);
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dkdv_kernel<D>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kv_lds);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dq_kernel<D>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, q_lds);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const int blocks128 = (p.n + 127) / 128;
+    FusedParams pk = p;
+    pk.list_ptr = csc_ptr;
+    pk.list_idx = csc_idx;
+    hipLaunchKernelGGL(bwd_dkdv_kernel<D>, dim3((unsigned)(blocks128 * bh)), dim3(kThreads), kv_lds, stream, pk);
+    FusedParams pq = p;
+    pq.list_ptr = csr_ptr;
+    pq.list_idx = csr_idx;
+    hipLaunchKernelGGL(bwd_dq_kernel<D>, dim3((unsigned)(blocks128 * bh)), dim3(kThreads), q_lds, stream, pq);
+    return hipGetLastError();
+}
+
+hipError_t launch_bwd_fused(int d, const FusedParams& p, const int32_t* csr_ptr, const int32_t* csr_idx,
+                            const int32_t* csc_ptr, const int32_t* csc_idx, hipStream_t stream) {
+    switch (d) {
+        case 64: return launch_bwd<64>(p, csr_ptr, csr_idx, csc_ptr, csc_idx, stream);
+        case 128: return launch_bwd<128>(p, csr_ptr, csr_idx, csc_ptr, csc_idx, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace attn

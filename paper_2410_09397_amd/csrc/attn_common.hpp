@@ -1,0 +1,161 @@
+// Shared device helpers for the gfx950 attention kernels: vector types, the LDS tile
+// layout, MFMA operand fetches and bf16 packing.  HIP device code only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace attn {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef short i16x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+#define ATTN_LDS __attribute__((address_space(3)))
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr int kThreads = 256;  // four 64-lane wavefronts per workgroup, one per SIMD
+
+// ---------------------------------------------------------------------------------------
+// 32x32x16 bf16 MFMA.  Operand layout (lane l, h = l / 32):
+//   A (32 x 16): row l % 32, k = 8h .. 8h+7        B (16 x 32): column l % 32, k = 8h .. 8h+7
+//   C (32 x 32): column l % 32, register i <-> row 8 (i / 4) + 4h + i % 4
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// Row of accumulator register i for a lane in half h.
+__device__ __forceinline__ int acc_row(int i, int h) { return 8 * (i >> 2) + 4 * h + (i & 3); }
+
+// Two fp32 -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32).
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    f32x2 v = {lo, hi};
+    bf16x2 r = __builtin_convertvector(v, bf16x2);
+    return __builtin_bit_cast(uint32_t, r);
+}
+
+// Registers 8s .. 8s+7 of an accumulator as one bf16 B operand.  Its k index (h, t) then
+// stands for accumulator row 16s + 8 (t / 4) + 4h + t % 4, which load_frag_t() mirrors.
+__device__ __forceinline__ bf16x8 acc_to_operand(const f32x16& c, int s) {
+    u32x4 r;
+    r[0] = pack_bf16(c[8 * s + 0], c[8 * s + 1]);
+    r[1] = pack_bf16(c[8 * s + 2], c[8 * s + 3]);
+    r[2] = pack_bf16(c[8 * s + 4], c[8 * s + 5]);
+    r[3] = pack_bf16(c[8 * s + 6], c[8 * s + 7]);
+    return __builtin_bit_cast(bf16x8, r);
+}
+
+// ---------------------------------------------------------------------------------------
+// LDS tile: R rows of D bf16, row-major, no padding, 16-byte chunks XOR-swizzled by row so
+// that both fetch patterns below spread over all 64 banks:
+//   - row-major fetch: 16 lanes read the same chunk column of 16 consecutive rows,
+//   - transposed fetch: 32 lanes read 4 consecutive rows x 4 consecutive chunks.
+// ---------------------------------------------------------------------------------------
+template <int D>
+__device__ __forceinline__ int swz(int row) {
+    if constexpr (D >= 128)
+        return ((row & 3) << 2) | ((row >> 2) & 3);
+    else
+        return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
+}
+
+// Byte offset of 16-byte chunk c (8 elements) of a tile row.
+template <int D>
+__device__ __forceinline__ int tile_off(int row, int c) {
+    return row * (D * 2) + ((c ^ swz<D>(row)) << 4);
+}
+
+// A (or B) operand whose k index runs along the tile's contiguous dimension:
+// lane l holds row row0 + l % 32, elements 16 ks + 8h .. +7.
+template <int D>
+__device__ __forceinline__ bf16x8 load_frag(const char* tile, int row0, int ks, int lane) {
+    const int row = row0 + (lane & 31);
+    return *reinterpret_cast<const bf16x8*>(tile + tile_off<D>(row, 2 * ks + (lane >> 5)));
+}
+
+// A operand whose k index runs along the tile's rows (the tile is read transposed):
+// lane l holds column col0 + l % 32 and, for t = 0..7, row row16 + 8 (t / 4) + 4h + t % 4.
+// Two ds_read_b64_tr_b16: within each group of 16 lanes, lane s supplies the address of
+// row + s / 4, columns 4 (s % 4) .. +3, and receives column s of the four rows.
+template <int D>
+__device__ __forceinline__ bf16x8 load_frag_t(const char* tile, int col0, int row16, int lane) {
+    const int s = lane & 15;
+    const int row = row16 + 4 * (lane >> 5) + (s >> 2);
+    const int col = col0 + 16 * ((lane >> 4) & 1) + 4 * (s & 3);
+    const int off0 = tile_off<D>(row, col >> 3) + ((col & 4) << 1);
+    const int off1 = tile_off<D>(row + 8, col >> 3) + ((col & 4) << 1);
+    i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 ATTN_LDS*)(tile + off0));
+    i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 ATTN_LDS*)(tile + off1));
+    typedef short i16x8 __attribute__((ext_vector_type(8)));
+    i16x8 r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, r);
+}
+
+// Cooperative copy of a [ROWS x D] bf16 tile: global (row stride `ld` elements) -> registers
+// -> swizzled LDS tile.  Rows at or beyond `rows_valid` read as zero.
+template <int D, int ROWS>
+struct TileCopy {
+    static constexpr int kChunksPerRow = D / 8;
+    static constexpr int kPerThread = ROWS * kChunksPerRow / kThreads;
+    static_assert(ROWS * kChunksPerRow % kThreads == 0, "tile must split evenly over the workgroup");
+    u32x4 regs[kPerThread];
+
+    __device__ __forceinline__ void fetch(const __bf16* base, long ld, int row_begin, int rows_valid, int tid) {
+#pragma unroll
+        for (int u = 0; u < kPerThread; ++u) {
+            const int q = tid + u * kThreads;
+            const int row = q / kChunksPerRow, c = q % kChunksPerRow;
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (row_begin + row < rows_valid)
+                v = *reinterpret_cast<const u32x4*>(base + (long)(row_begin + row) * ld + c * 8);
+            regs[u] = v;
+        }
+    }
+    __device__ __forceinline__ void store(char* tile, int tid) const {
+#pragma unroll
+        for (int u = 0; u < kPerThread; ++u) {
+            const int q = tid + u * kThreads;
+            const int row = q / kChunksPerRow, c = q % kChunksPerRow;
+            *reinterpret_cast<u32x4*>(tile + tile_off<D>(row, c)) = regs[u];
+        }
+    }
+};
+
+// Head and tile decoding shared by the kernels.  Workgroups are handed to the 8 XCDs round
+// robin by linear id, so ids congruent mod 8 share an L2: all tiles of one (batch, head) are
+// given to one XCD when the head count allows it.
+__device__ __forceinline__ void decode_block(int linear, int tiles, int bh_total, int& bh, int& tile) {
+    if ((bh_total & 7) == 0) {
+        const int xcd = linear & 7, slot = linear >> 3;
+        bh = (slot / tiles) * 8 + xcd;
+        tile = slot % tiles;
+    } else {
+        bh = linear / tiles;
+        tile = linear % tiles;
+    }
+}
+
+// Kernel arguments common to the fused kernels.  Strides are in elements.
+struct FusedParams {
+    const __bf16 *Q, *K, *V, *O, *dO;
+    __bf16 *Oout, *dQ, *dK, *dV;
+    const float* LSE;    // [batch*heads, n] natural-log sums (backward input)
+    float* LSEout;       // forward output
+    float* delta;        // [batch*heads, n] rowsum(dO o O), workspace
+    long stride_b, stride_h, stride_n;
+    int batch, heads, n;
+    float scale;
+    int causal;
+    // block-sparse lists (nullptr = dense): ptr/idx give, per 128-row block of the resident
+    // operand, the 128-row blocks of the streamed operand that are visible, ascending.
+    const int32_t *list_ptr, *list_idx;
+};
+
+}  // namespace attn

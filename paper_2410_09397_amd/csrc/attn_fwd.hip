@@ -1,0 +1,197 @@
+// Fused forward for d <= 128: O = diag(l)^{-1} exp(scale Q K^T) V and LSE = log l (forward
+// definition, Sec. 3.1; A, l, f, O of App. B.4), evaluated per block of 128 queries with a
+// running maximum so that no n x n matrix is formed.  The paper gives no forward algorithm;
+// the streaming-softmax tiling is prior art, the kernel is written for gfx950.
+#include "attn_common.hpp"
+#include "attn_internal.hpp"
+
+namespace attn {
+
+// Wave w owns queries i0 + 32w .. +31 (Q rows resident in registers as B operands).
+// Per key tile (64 keys, two halves T):
+//   S^T[T] = K_T Q_w^T                 accumulator: lane <-> query, register <-> key
+//   m, l   : running row maximum and sum, one scalar per lane (both lane halves of a query
+//            see the same maximum; their partial sums are added at the end)
+//   O_w^T += V_T^T P^T                 V^T from transposed LDS reads, P^T straight from registers
+template <int D>
+__global__ void __launch_bounds__(kThreads, 1) fwd_kernel(FusedParams p) {
+    constexpr int BR = 128, BC = 64, KS = D / 16, MT = D / 32;
+    constexpr int kTileBytes = BC * D * 2;
+    constexpr int kStageBytes = 2 * kTileBytes;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, h = lane >> 5, l32 = lane & 31;
+    const int q_blocks = (p.n + BR - 1) / BR;
+    int bh, blk;
+    decode_block(blockIdx.x, q_blocks, p.batch * p.heads, bh, blk);
+    const int ib = p.causal ? q_blocks - 1 - blk : blk;  // causal: longest rows first
+    const long base = (long)(bh / p.heads) * p.stride_b + (long)(bh % p.heads) * p.stride_h;
+    const long ld = p.stride_n;
+    const int i0 = ib * BR;
+
+    int n_it, lp0 = 0;
+    if (p.list_ptr) {
+        lp0 = p.list_ptr[ib];
+        n_it = (p.list_ptr[ib + 1] - lp0) * (128 / BC);
+    } else {
+        const int k_end = p.causal ? min(p.n, i0 + BR) : p.n;
+        n_it = (k_end + BC - 1) / BC;
+    }
+    auto tile_start = [&](int it) -> int {
+        if (p.list_ptr) return p.list_idx[lp0 + it / (128 / BC)] * 128 + (it % (128 / BC)) * BC;
+        return it * BC;
+    };
+
+    const int q = i0 + 32 * w + l32;
+    const bool q_ok = q < p.n;
+    bf16x8 qf[KS];
+    {
+        const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            qf[ks] = zero;
+            if (q_ok) qf[ks] = *reinterpret_cast<const bf16x8*>(p.Q + base + (long)q * ld + 16 * ks + 8 * h);
+        }
+    }
+
+    f32x16 o[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[mt][i] = 0.f;
+    float m_run = -__builtin_inff();  // running maximum of c * s (log2 domain)
+    float l_run = 0.f;                // this lane's share of sum exp2(c s - m_run)
+
+    const float c = p.scale * kLog2e;
+    TileCopy<D, BC> ck, cv;
+    auto fetch = [&](int j0) {
+        ck.fetch(p.K + base, ld, j0, p.n, tid);
+        cv.fetch(p.V + base, ld, j0, p.n, tid);
+    };
+    auto commit = [&](int stage) {
+        char* s = smem + stage * kStageBytes;
+        ck.store(s, tid);
+        cv.store(s + kTileBytes, tid);
+    };
+    if (n_it > 0) {
+        fetch(tile_start(0));
+        commit(0);
+    }
+    __syncthreads();
+
+    for (int it = 0; it < n_it; ++it) {
+        const int j0 = tile_start(it);
+        const bool more = it + 1 < n_it;
+        if (more) fetch(tile_start(it + 1));
+        const char* ks_t = smem + (it & 1) * kStageBytes;
+        const char* vs_t = ks_t + kTileBytes;
+
+        const bool skip = p.causal && (i0 + 32 * w + 31 < j0);
+        if (!skip) {
+            f32x16 st[2];
+#pragma unroll
+            for (int T = 0; T < 2; ++T)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) st[T][i] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int T = 0; T < 2; ++T) st[T] = mfma32(load_frag<D>(ks_t, 32 * T, ks, lane), qf[ks], st[T]);
+
+            const bool need_mask = (p.causal && (j0 + BC - 1 > i0 + 32 * w)) || (j0 + BC > p.n);
+            float mx = -__builtin_inff();
+#pragma unroll
+            for (int T = 0; T < 2; ++T)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    float x = st[T][i] * c;
+                    if (need_mask) {
+                        const int key = j0 + 32 * T + acc_row(i, h);
+                        if (key >= p.n || (p.causal && key > q)) x = -__builtin_inff();
+                    }
+                    st[T][i] = x;
+                    mx = fmaxf(mx, x);
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float m_new = fmaxf(m_run, mx);
+            const float m_use = (m_new == -__builtin_inff()) ? 0.f : m_new;  // nothing visible yet
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+            m_run = m_new;
+            float sum = 0.f;
+#pragma unroll
+            for (int T = 0; T < 2; ++T)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const float pv = __builtin_amdgcn_exp2f(st[T][i] - m_use);
+                    st[T][i] = pv;
+                    sum += pv;
+                }
+            l_run = l_run * alpha + sum;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o[mt][i] *= alpha;
+            bf16x8 pb[2][2];
+#pragma unroll
+            for (int T = 0; T < 2; ++T)
+#pragma unroll
+                for (int ss = 0; ss < 2; ++ss) pb[T][ss] = acc_to_operand(st[T], ss);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int T = 0; T < 2; ++T)
+#pragma unroll
+                    for (int ss = 0; ss < 2; ++ss)
+                        o[mt] = mfma32(load_frag_t<D>(vs_t, 32 * mt, 32 * T + 16 * ss, lane), pb[T][ss], o[mt]);
+        }
+        if (more) commit((it + 1) & 1);
+        __syncthreads();
+    }
+
+    const float l = l_run + __shfl_xor(l_run, 32, 64);
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+    if (q_ok) {
+        __bf16* row = p.Oout + base + (long)q * ld;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                u32x2 a;
+                a[0] = pack_bf16(o[mt][4 * g + 0] * inv, o[mt][4 * g + 1] * inv);
+                a[1] = pack_bf16(o[mt][4 * g + 2] * inv, o[mt][4 * g + 3] * inv);
+                *reinterpret_cast<u32x2*>(row + 32 * mt + 8 * g + 4 * h) = a;
+            }
+        if (h == 0)
+            p.LSEout[(long)bh * p.n + q] = l > 0.f ? (m_run + __builtin_amdgcn_logf(l)) * kLn2 : -__builtin_inff();
+    }
+}
+
+template <int D>
+static hipError_t launch_fwd(const FusedParams& p, const int32_t* csr_ptr, const int32_t* csr_idx,
+                             hipStream_t stream) {
+    constexpr int lds = 2 * (2 * 64 * D * 2);
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fwd_kernel<D>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    FusedParams pf = p;
+    pf.list_ptr = csr_ptr;
+    pf.list_idx = csr_idx;
+    const int blocks = (p.n + 127) / 128 * p.batch * p.heads;
+    hipLaunchKernelGGL(fwd_kernel<D>, dim3((unsigned)blocks), dim3(kThreads), lds, stream, pf);
+    return hipGetLastError();
+}
+
+hipError_t launch_fwd_fused(int d, const FusedParams& p, const int32_t* csr_ptr, const int32_t* csr_idx,
+                            hipStream_t stream) {
+    switch (d) {
+        case 64: return launch_fwd<64>(p, csr_ptr, csr_idx, stream);
+        case 128: return launch_fwd<128>(p, csr_ptr, csr_idx, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace attn

@@ -1,0 +1,50 @@
+"""Shared pieces of the GPU parity tests: upload, oracle reference, error metric."""
+import numpy as np
+
+from oracle import attn_oracle as orc
+from paper_2410_09397_amd import synth
+
+# Tolerances of the parity gate: max |x - ref| / max |ref| per output tensor.
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+# LSE is compared absolutely (it is fp32 on both storage types; the bf16 path accumulates
+# bf16 x bf16 products exactly in fp32, so only exp/log rounding and summation order differ).
+LSE_TOL = {"f32": 1e-4, "bf16": 2e-3}
+
+
+def torch_dtype(name):
+    import torch
+    return {"f32": torch.float32, "bf16": torch.bfloat16}[name]
+
+
+def to_dev(x, dtype):
+    """float32 numpy array holding storage-dtype values -> cuda tensor of that dtype."""
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to("cuda").to(torch_dtype(dtype))
+
+
+def to_np(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def rel_err(x, ref):
+    ref = np.asarray(ref, dtype=np.float64)
+    den = np.abs(ref).max()
+    return float(np.abs(np.asarray(x, dtype=np.float64) - ref).max() / (den if den > 0 else 1.0))
+
+
+def round_storage(x, dtype):
+    """float64 array -> values representable in the storage dtype (as float32)."""
+    x32 = np.asarray(x, dtype=np.float32)
+    return synth.round_to_bf16(x32) if dtype == "bf16" else x32
+
+
+def oracle_reference(w, inp):
+    """Oracle forward, then oracle backward fed with the O / LSE the GPU backward will be given
+    in the isolated test (rounded to the storage type / to fp32)."""
+    m = dict(causal=w.causal, keep=inp["keep"], block=w.block)
+    O, LSE = orc.attn_fwd(inp["Q"], inp["K"], inp["V"], w.scale, **m)
+    O_in = round_storage(O, w.dtype)
+    LSE_in = LSE.astype(np.float32)
+    grads_iso = orc.attn_bwd(inp["Q"], inp["K"], inp["V"], O_in, inp["dO"], LSE_in, w.scale, **m)
+    grads_exact = orc.attn_bwd(inp["Q"], inp["K"], inp["V"], O, inp["dO"], LSE, w.scale, **m)
+    return dict(O=O, LSE=LSE, O_in=O_in, LSE_in=LSE_in, iso=grads_iso, exact=grads_exact)
