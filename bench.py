@@ -1,0 +1,136 @@
+"""Benchmark of the attention hot path on one MI355X.
+
+A step is one pass of the whole path on one batch of seeded synthetic input that is already
+resident in HBM: attn_fwd (O, LSE) followed by attn_bwd / attn_bwd_blocksparse (delta, dK/dV,
+dQ).  The reported value is the metric's attention-backward TFLOP/s: algorithmic backward
+FLOPs (five n x n x d contractions over visible pairs) divided by the backward's share of the
+timed steps, measured with HIP events on the launch stream; ms_per_step covers forward plus
+backward.  Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "attention-backward TFLOP/s (bf16, 1 GPU) + HBM bytes vs paper I/O bound"
+PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}  # MI355X dense MFMA bf16; fp32 vector
+
+
+def cpu_baseline(w, seconds_hint=20.0):
+    """The oracle's backward, timed on a bounded sample of the workload on the host cores."""
+    import numpy as np
+    from oracle import attn_oracle as orc
+    from paper_2410_09397_amd import synth
+    cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)))
+    n_s = min(w.n, 4096 if w.d <= 128 else 2048)
+    heads_s = max(1, min(w.batch * w.heads, 2 * cores))
+    ws = w.small(name=w.name + "_cpu_sample", batch=1, heads=heads_s, n=n_s)
+    inp = synth.make_inputs(ws)
+    m = dict(causal=ws.causal, keep=inp["keep"], block=ws.block)
+    O, LSE = orc.attn_fwd(inp["Q"], inp["K"], inp["V"], ws.scale, **m)
+    t0 = time.perf_counter()
+    orc.attn_bwd(inp["Q"], inp["K"], inp["V"], O, inp["dO"], LSE, ws.scale, **m)
+    dt = time.perf_counter() - t0
+    return {"value": ws.bwd_flops() / dt * 1e-12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": "oracle float64 backward on %d heads of the same workload with n cut to %d "
+                      "(d=%d, %s%s), %.1f s" % (heads_s, n_s, ws.d, "causal" if ws.causal else "non-causal",
+                                                ", block-sparse" if ws.sparse else "", dt)}
+
+
+def load_traffic(name):
+    """HBM bytes per backward launch from the committed rocprofv3 --pmc summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if not os.path.exists(path):
+        return None
+    with open(path) as fh:
+        return json.load(fh).get(name)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=3, help="1..5, index into the metric's configurations")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy, so that HBM byte counters read in the "
+                         "same profiler run can be scaled by a transfer of known size")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+
+    import torch
+    from paper_2410_09397_amd import attn, io_bound, synth
+    w = synth.workload(args.workload)
+    dt = {"bf16": torch.bfloat16, "f32": torch.float32}[w.dtype]
+    inp = synth.make_inputs(w)
+    Q, K, V, dO = (torch.from_numpy(inp[t]).to("cuda").to(dt) for t in ("Q", "K", "V", "dO"))
+    mask = attn.BlockMask(inp["keep"], w.block, w.n) if w.sparse else None
+    O = torch.empty_like(Q)
+    LSE = torch.empty(Q.shape[:3], dtype=torch.float32, device="cuda")
+    grads = tuple(torch.empty_like(Q) for _ in range(3))
+    desc = attn._desc(Q, w.scale, w.causal)
+    ws = torch.empty(max(attn.attn_workspace_bytes(desc, mask), 256), dtype=torch.uint8, device="cuda")
+
+    def step(ev=None):
+        attn.attn_fwd(Q, K, V, w.scale, causal=w.causal, mask=mask, out=(O, LSE), workspace=ws)
+        if ev:
+            ev[0].record()
+        if mask is not None:
+            attn.attn_bwd_blocksparse(Q, K, V, O, dO, LSE, w.scale, mask, causal=w.causal, out=grads, workspace=ws)
+        else:
+            attn.attn_bwd(Q, K, V, O, dO, LSE, w.scale, causal=w.causal, out=grads, workspace=ws)
+        if ev:
+            ev[1].record()
+
+    for _ in range(args.warmup):
+        step()
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(events[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    if args.calibrate_copy:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")  # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    bwd_ms = sum(a.elapsed_time(b) for a, b in events) / args.steps
+    fwd_ms = ms_per_step - bwd_ms
+    bwd_tflops = w.bwd_flops() / (bwd_ms * 1e-3) * 1e-12
+
+    peak = PEAK_TFLOPS[w.dtype]
+    traffic = load_traffic(w.name)
+    bound = io_bound.report(w)
+    out = {
+        "metric": METRIC, "value": bwd_tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "heads": w.heads, "n": w.n, "d": w.d,
+                   "causal": w.causal, "block_sparse": w.sparse, "step": "attn_fwd + attn_bwd"},
+        "bwd_ms": bwd_ms, "fwd_ms": fwd_ms, "fwd_tflops": w.fwd_flops() / (fwd_ms * 1e-3) * 1e-12,
+        "step_tflops": (w.fwd_flops() + w.bwd_flops()) / (ms_per_step * 1e-3) * 1e-12,
+        "roofline": {"bound": "mfma" if w.dtype == "bf16" else "alu", "kernel": "attn_bwd (delta + dK/dV + dQ kernels)",
+                     "achieved": bwd_tflops, "peak": peak, "unit": "TFLOP/s", "frac": bwd_tflops / peak,
+                     "traffic": traffic},
+        "io_bound": bound,
+        "traffic_over_yardstick": (traffic / bound["yardstick_bytes"]) if traffic else None,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -26,8 +26,10 @@
  *   - Arguments are validated on the host before anything is launched; a failed call launches
  *     nothing and leaves outputs untouched.  batch * heads * n == 0 is a valid empty call.
  *   - Supported: d a multiple of 8 for ATTN_BF16 (pointers and strides 16-byte aligned), any d
- *     for ATTN_F32, 1 <= d <= 512.  ATTN_BF16 with d in {64, 128} (block masks: block == 128) runs
- *     the bf16-MFMA kernels with fp32 accumulation; ATTN_F32 runs fp32 FMA kernels only.
+ *     for ATTN_F32, 1 <= d <= 512.  ATTN_BF16 runs bf16-MFMA kernels with fp32 accumulation for
+ *     d in {64, 128} (block masks: block == 128; fused, nothing n x n leaves the chip) and for
+ *     d in {256, 512} without block mask and n <= 32768 (four-phase path through the workspace);
+ *     every other supported case, ATTN_F32 always, runs fp32 FMA kernels.
  */
 #ifndef ATTN_MI355X_H
 #define ATTN_MI355X_H
@@ -71,13 +73,17 @@ typedef struct {
     const int32_t *col_ptr, *row_idx;
 } attn_blockmask;
 
-/* Bytes of device scratch attn_bwd / attn_bwd_blocksparse need for `desc` (0 if desc is
- * invalid).  attn_fwd needs none. */
+/* Bytes of device scratch that attn_fwd, attn_bwd and attn_bwd_blocksparse need for `desc`
+ * (one figure that covers all three; 0 if desc or mask is invalid).  For d <= 128 it holds the
+ * [batch, heads, n] row sums v; for d > 128 (App. C path) also the n x n matrices f and p of
+ * every (batch, head) in bf16, with n rounded up to 128. */
 size_t attn_workspace_bytes(const attn_desc *desc, const attn_blockmask *mask /* nullable */);
 
-/* Forward: writes O [batch, heads, n, d] and LSE [batch, heads, n].  `mask` may be NULL. */
+/* Forward: writes O [batch, heads, n, d] and LSE [batch, heads, n].  `mask` may be NULL.
+ * `workspace` is read only when d > 128 and may be NULL otherwise. */
 attn_status attn_fwd(const attn_desc *desc, const attn_blockmask *mask, const void *Q,
-                     const void *K, const void *V, void *O, float *LSE, void *stream);
+                     const void *K, const void *V, void *O, float *LSE, void *workspace,
+                     size_t workspace_bytes, void *stream);
 
 /* Backward without block mask: dQ, dK, dV from Q, K, V, the forward's O and LSE, and dO. */
 attn_status attn_bwd(const attn_desc *desc, const void *Q, const void *K, const void *V,

@@ -54,7 +54,7 @@ def lib():
         L.attn_workspace_bytes.restype = ctypes.c_size_t
         L.attn_workspace_bytes.argtypes = [dp, mp]
         L.attn_fwd.restype = ctypes.c_int
-        L.attn_fwd.argtypes = [dp, mp, vp, vp, vp, vp, vp, vp]
+        L.attn_fwd.argtypes = [dp, mp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.attn_bwd.restype = ctypes.c_int
         L.attn_bwd.argtypes = [dp] + [vp] * 9 + [vp, ctypes.c_size_t, vp]
         L.attn_bwd_blocksparse.restype = ctypes.c_int
@@ -132,16 +132,25 @@ def attn_workspace_bytes(desc, mask=None):
     return lib().attn_workspace_bytes(ctypes.byref(desc), ctypes.byref(mask.c) if mask is not None else None)
 
 
-def attn_fwd(Q, K, V, scale, causal=False, mask=None, stream=None, out=None):
+def _workspace(desc, mask, workspace, device):
+    import torch
+    if workspace is None:
+        workspace = torch.empty(max(attn_workspace_bytes(desc, mask), 256), dtype=torch.uint8, device=device)
+    return workspace
+
+
+def attn_fwd(Q, K, V, scale, causal=False, mask=None, stream=None, out=None, workspace=None):
     """O, LSE = forward(Q, K, V) on the GPU.  Q, K, V: cuda tensors [batch, heads, n, d]."""
     import torch
     _same_layout(Q, K, V)
     desc = _desc(Q, scale, causal)
+    workspace = _workspace(desc, mask, workspace, Q.device)
     O = out[0] if out is not None else torch.empty_like(Q)
     LSE = out[1] if out is not None else torch.empty(Q.shape[:3], dtype=torch.float32, device=Q.device)
     _same_layout(Q, O)
     st = lib().attn_fwd(ctypes.byref(desc), ctypes.byref(mask.c) if mask is not None else None,
-                        Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), LSE.data_ptr(), _stream(stream))
+                        Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), LSE.data_ptr(),
+                        workspace.data_ptr(), workspace.numel(), _stream(stream))
     if st != ATTN_OK:
         raise AttnError(st, "attn_fwd")
     return O, LSE
@@ -155,9 +164,7 @@ def _bwd(name, Q, K, V, O, dO, LSE, scale, causal, mask, stream, out, workspace)
     _same_layout(Q, dQ, dK, dV)
     if LSE.dtype != torch.float32 or not LSE.is_contiguous() or LSE.shape != Q.shape[:3]:
         raise ValueError("LSE must be a contiguous float32 [batch, heads, n] tensor")
-    need = attn_workspace_bytes(desc, mask)
-    if workspace is None:
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=Q.device)
+    workspace = _workspace(desc, mask, workspace, Q.device)
     args = [Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), dO.data_ptr(), LSE.data_ptr(),
             dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream(stream)]
     if name == "attn_bwd":

@@ -11,6 +11,7 @@ namespace {
 
 using attn::FusedParams;
 using attn::GenericParams;
+using attn::LargeDParams;
 
 enum class Path { kFused, kLargeD, kGeneric };
 
@@ -44,10 +45,34 @@ bool is_empty(const attn_desc* d) { return (long)d->batch * d->heads * d->n == 0
 
 Path pick_path(const attn_desc* d, const attn_blockmask* m) {
     if (d->dtype == ATTN_BF16 && (d->d == 64 || d->d == 128) && (!m || m->block == 128)) return Path::kFused;
+    if (d->dtype == ATTN_BF16 && (d->d == 256 || d->d == 512) && !m && d->n <= 32768) return Path::kLargeD;
     return Path::kGeneric;
 }
 
 size_t delta_bytes(const attn_desc* d) { return round_up((size_t)d->batch * d->heads * d->n * sizeof(float), 256); }
+
+// Workspace layout of the large-d path.  Backward: [delta][P][dS]; forward: [stat_m][stat_l][P].
+size_t npad_of(const attn_desc* d) { return round_up((size_t)d->n, 128); }
+size_t nn_bytes(const attn_desc* d) { return (size_t)d->batch * d->heads * npad_of(d) * npad_of(d) * 2; }
+size_t stat_bytes(const attn_desc* d) {
+    return round_up((size_t)d->batch * d->heads * d->n * (npad_of(d) / 64) * sizeof(float), 256);
+}
+
+LargeDParams larged_params(const attn_desc* d) {
+    LargeDParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.stride_b = d->stride_b;
+    p.stride_h = d->stride_h;
+    p.stride_n = d->stride_n;
+    p.batch = d->batch;
+    p.heads = d->heads;
+    p.n = d->n;
+    p.d = d->d;
+    p.npad = (int)npad_of(d);
+    p.scale = d->scale;
+    p.causal = d->causal;
+    return p;
+}
 
 FusedParams fused_params(const attn_desc* d) {
     FusedParams p;
@@ -119,6 +144,28 @@ attn_status bwd_impl(const attn_desc* desc, const attn_blockmask* mask, const vo
                                        mask ? mask->col_ptr : nullptr, mask ? mask->row_idx : nullptr, s);
             break;
         }
+        case Path::kLargeD: {
+            char* ws = static_cast<char*>(workspace);
+            FusedParams fp = fused_params(desc);
+            fp.O = static_cast<const __bf16*>(O);
+            fp.dO = static_cast<const __bf16*>(dO);
+            fp.delta = reinterpret_cast<float*>(ws);
+            attn::launch_delta(fp, desc->d, s);
+            LargeDParams p = larged_params(desc);
+            p.Q = static_cast<const __bf16*>(Q);
+            p.K = static_cast<const __bf16*>(K);
+            p.V = static_cast<const __bf16*>(V);
+            p.dO = static_cast<const __bf16*>(dO);
+            p.dQ = static_cast<__bf16*>(dQ);
+            p.dK = static_cast<__bf16*>(dK);
+            p.dV = static_cast<__bf16*>(dV);
+            p.LSE = LSE;
+            p.delta = fp.delta;
+            p.P = reinterpret_cast<__bf16*>(ws + delta_bytes(desc));
+            p.dS = reinterpret_cast<__bf16*>(ws + delta_bytes(desc) + nn_bytes(desc));
+            e = attn::launch_larged(true, p, s);
+            break;
+        }
         default: {
             GenericParams p = generic_params(desc, mask);
             p.Q = Q;
@@ -146,11 +193,16 @@ extern "C" {
 size_t attn_workspace_bytes(const attn_desc* desc, const attn_blockmask* mask) {
     if (check_desc(desc) != ATTN_OK || check_mask(desc, mask) != ATTN_OK) return 0;
     if (is_empty(desc)) return 256;
+    if (pick_path(desc, mask) == Path::kLargeD) {
+        const size_t bwd = delta_bytes(desc) + 2 * nn_bytes(desc);
+        const size_t fwd = 2 * stat_bytes(desc) + nn_bytes(desc);
+        return bwd > fwd ? bwd : fwd;
+    }
     return delta_bytes(desc);
 }
 
 attn_status attn_fwd(const attn_desc* desc, const attn_blockmask* mask, const void* Q, const void* K,
-                     const void* V, void* O, float* LSE, void* stream) {
+                     const void* V, void* O, float* LSE, void* workspace, size_t workspace_bytes, void* stream) {
     attn_status st = check_desc(desc);
     if (st != ATTN_OK) return st;
     st = check_mask(desc, mask);
@@ -159,9 +211,13 @@ attn_status attn_fwd(const attn_desc* desc, const attn_blockmask* mask, const vo
     if (!Q || !K || !V || !O || !LSE) return ATTN_ERR_INVALID_ARG;
     if (desc->dtype == ATTN_BF16 && !(aligned16(Q) && aligned16(K) && aligned16(V) && aligned16(O)))
         return ATTN_ERR_INVALID_ARG;
+    const Path path = pick_path(desc, mask);
+    if (path == Path::kLargeD &&
+        (!workspace || workspace_bytes < attn_workspace_bytes(desc, mask) || !aligned16(workspace)))
+        return ATTN_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e;
-    switch (pick_path(desc, mask)) {
+    switch (path) {
         case Path::kFused: {
             FusedParams p = fused_params(desc);
             p.Q = static_cast<const __bf16*>(Q);
@@ -170,6 +226,20 @@ attn_status attn_fwd(const attn_desc* desc, const attn_blockmask* mask, const vo
             p.Oout = static_cast<__bf16*>(O);
             p.LSEout = LSE;
             e = attn::launch_fwd_fused(desc->d, p, mask ? mask->row_ptr : nullptr, mask ? mask->col_idx : nullptr, s);
+            break;
+        }
+        case Path::kLargeD: {
+            char* ws = static_cast<char*>(workspace);
+            LargeDParams p = larged_params(desc);
+            p.Q = static_cast<const __bf16*>(Q);
+            p.K = static_cast<const __bf16*>(K);
+            p.V = static_cast<const __bf16*>(V);
+            p.Oout = static_cast<__bf16*>(O);
+            p.LSEout = LSE;
+            p.stat_m = reinterpret_cast<float*>(ws);
+            p.stat_l = reinterpret_cast<float*>(ws + stat_bytes(desc));
+            p.P = reinterpret_cast<__bf16*>(ws + 2 * stat_bytes(desc));
+            e = attn::launch_larged(false, p, s);
             break;
         }
         default: {

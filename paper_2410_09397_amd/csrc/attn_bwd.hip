@@ -13,8 +13,7 @@ namespace attn {
 
 // --------------------------------------------------------------------------------- delta
 // One wavefront per row; lanes read 16-byte chunks and the row sum is a shuffle reduction.
-template <int D>
-__global__ void __launch_bounds__(kThreads) delta_kernel(FusedParams p) {
+__global__ void __launch_bounds__(kThreads) delta_kernel(FusedParams p, int d) {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const long rows = (long)p.batch * p.heads * p.n;
     const long r = (long)blockIdx.x * 4 + w;
@@ -22,7 +21,7 @@ __global__ void __launch_bounds__(kThreads) delta_kernel(FusedParams p) {
     const int bh = (int)(r / p.n), i = (int)(r % p.n);
     const long base = (long)(bh / p.heads) * p.stride_b + (long)(bh % p.heads) * p.stride_h + (long)i * p.stride_n;
     float acc = 0.f;
-    for (int c = lane; c < D / 8; c += 64) {
+    for (int c = lane; c < d / 8; c += 64) {
         bf16x8 o = *reinterpret_cast<const bf16x8*>(p.O + base + c * 8);
         bf16x8 g = *reinterpret_cast<const bf16x8*>(p.dO + base + c * 8);
 #pragma unroll
@@ -355,12 +354,16 @@ __global__ void __launch_bounds__(kThreads, 1) bwd_dq_kernel(FusedParams p) {
 }
 
 // ------------------------------------------------------------------------------ launchers
+void launch_delta(const FusedParams& p, int d, hipStream_t stream) {
+    const long rows = (long)p.batch * p.heads * p.n;
+    hipLaunchKernelGGL(delta_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(kThreads), 0, stream, p, d);
+}
+
 template <int D>
 static hipError_t launch_bwd(const FusedParams& p, const int32_t* csr_ptr, const int32_t* csr_idx,
                              const int32_t* csc_ptr, const int32_t* csc_idx, hipStream_t stream) {
     const int bh = p.batch * p.heads;
-    const long rows = (long)bh * p.n;
-    hipLaunchKernelGGL(delta_kernel<D>, dim3((unsigned)((rows + 3) / 4)), dim3(kThreads), 0, stream, p);
+    launch_delta(p, D, stream);
 
     constexpr int kv_lds = 2 * (2 * 64 * D * 2 + 2 * 64 * 4);
     constexpr int q_lds = 2 * (2 * 64 * D * 2);

@@ -62,8 +62,10 @@ template <int D>
 __device__ __forceinline__ int swz(int row) {
     if constexpr (D >= 128)
         return ((row & 3) << 2) | ((row >> 2) & 3);
-    else
+    else if constexpr (D == 64)
         return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
+    else  // D == 32: four chunks per row, only the row-major fetch is used
+        return (row >> 2) & 3;
 }
 
 // Byte offset of 16-byte chunk c (8 elements) of a tile row.

@@ -12,6 +12,26 @@ hipError_t launch_fwd_fused(int d, const FusedParams& p, const int32_t* csr_ptr,
 hipError_t launch_bwd_fused(int d, const FusedParams& p, const int32_t* csr_ptr, const int32_t* csr_idx,
                             const int32_t* csc_ptr, const int32_t* csc_idx, hipStream_t stream);
 
+// delta[b, h, i] = sum_k dO_ik O_ik for bf16 tensors (p.O, p.dO, p.delta), any d % 8 == 0.
+void launch_delta(const FusedParams& p, int d, hipStream_t stream);
+
+// Arguments of the large-d path (bf16, d in {256, 512}, no block mask).  P and dS are n x n
+// matrices per (batch, head) with row pitch npad = n rounded up to 128, in the workspace.
+struct LargeDParams {
+    const __bf16 *Q, *K, *V, *dO;
+    __bf16 *Oout, *dQ, *dK, *dV;
+    const float* LSE;   // backward input
+    float* LSEout;      // forward output
+    const float* delta; // backward: rowsum(dO o O)
+    __bf16 *P, *dS;
+    float *stat_m, *stat_l;  // forward: per 64-key chunk row maximum and sum, [bh][n][npad / 64]
+    long stride_b, stride_h, stride_n;
+    int batch, heads, n, d, npad;
+    float scale;
+    int causal;
+};
+hipError_t launch_larged(bool backward, const LargeDParams& p, hipStream_t stream);
+
 // Arguments of the generic fp32-arithmetic kernels (any n, d <= 512, any mask block edge).
 struct GenericParams {
     const void *Q, *K, *V, *O_in, *dO;

@@ -1,0 +1,364 @@
+// Large-d path (d in {256, 512}): the regime where a d x d working set no longer fits the
+// per-CU LDS and register budget (the paper's small-cache case, M = o(d^2)).  It follows the
+// four-phase small-cache algorithm of App. C: square tiles with the contraction loop split
+// into chunks, and the n x n matrices f (here P) and p (here dS) written to memory between
+// the phases:
+//   scores kernel : S^T = K Q^T and dP^T = V dO^T tile by tile with a k-loop over d-chunks
+//                   (phases 1 and 2), then f = exp(S - LSE) and p = f o (q - v) in the epilogue
+//                   (phase 3, one sweep because v = rowsum(dO o O) is precomputed) -> P, dS in HBM
+//   gemm kernel   : dV = P^T dO, dK = scale dS^T Q, dQ = scale dS K as tiled products with the
+//                   k-loop over n (phase 4 written for dQ/dK/dV instead of A_1^T p A_2)
+// The forward uses the same kernels: partial row statistics of S per 64-key chunk, a combine
+// step for LSE, P = exp(S - LSE) written to HBM, and O = P V.
+#include "attn_common.hpp"
+#include "attn_internal.hpp"
+
+namespace attn {
+
+namespace {
+
+constexpr uint32_t kRsrcFlags = 0x00020000;  // raw buffer, 32-bit data format
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, kRsrcFlags);
+}
+
+// Cooperative copy of a [ROWS x COLS] bf16 tile through registers into a swizzled LDS tile.
+// Buffer loads return zero beyond the resource's size, so ragged edges need no branches.
+template <int COLS, int ROWS>
+struct BufTile {
+    static constexpr int kCPR = COLS / 8;
+    static constexpr int kPer = ROWS * kCPR / kThreads;
+    static_assert(ROWS * kCPR % kThreads == 0, "tile must split evenly over the workgroup");
+    u32x4 regs[kPer];
+    __device__ __forceinline__ void fetch(__amdgpu_buffer_rsrc_t r, uint32_t row0, uint32_t col0, uint32_t ld_bytes,
+                                          int tid) {
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+            const int q = tid + u * kThreads;
+            const uint32_t row = q / kCPR, c = q % kCPR;
+            regs[u] = __builtin_amdgcn_raw_buffer_load_b128(r, (row0 + row) * ld_bytes + (col0 + 8 * c) * 2, 0, 0);
+        }
+    }
+    __device__ __forceinline__ void store(char* tile, int tid) const {
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+            const int q = tid + u * kThreads;
+            *reinterpret_cast<u32x4*>(tile + tile_off<COLS>(q / kCPR, q % kCPR)) = regs[u];
+        }
+    }
+};
+
+// Operand whose k index runs along the tile's contiguous dimension, but with the k order of
+// load_frag_t (element t of half h <-> column 16 ks + 8 (t / 4) + 4h + t % 4), for products
+// whose other operand is read transposed.
+template <int D>
+__device__ __forceinline__ bf16x8 load_frag_perm(const char* tile, int row0, int ks, int lane) {
+    const int row = row0 + (lane & 31), h = lane >> 5;
+    const u32x2 lo = *reinterpret_cast<const u32x2*>(tile + tile_off<D>(row, 2 * ks) + 8 * h);
+    const u32x2 hi = *reinterpret_cast<const u32x2*>(tile + tile_off<D>(row, 2 * ks + 1) + 8 * h);
+    u32x4 r = {lo[0], lo[1], hi[0], hi[1]};
+    return __builtin_bit_cast(bf16x8, r);
+}
+
+__device__ __forceinline__ void zero_acc(f32x16 (&c)[2][2]) {
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) c[a][b][i] = 0.f;
+}
+
+}  // namespace
+
+enum ScoreMode { kStats = 0, kProbs = 1, kBackward = 2 };
+
+// One workgroup: a 128 (keys) x 128 (queries) tile of S^T (and dP^T), waves in a 2 x 2 grid of
+// 64 x 64 sub-tiles.  Accumulator: lane <-> query, register <-> key.
+template <int MODE>
+__global__ void __launch_bounds__(kThreads, 2) ld_scores_kernel(LargeDParams p) {
+    constexpr int BK = 32;
+    constexpr int kTile = 128 * BK * 2;                       // bytes per operand tile
+    constexpr int kOps = MODE == kBackward ? 4 : 2;           // K, Q (+ V, dO)
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, h = lane >> 5, l32 = lane & 31;
+    const int wm = w >> 1, wn = w & 1;
+    const int nb = p.npad / 128;
+    const int bh = blockIdx.z;
+    int kb = blockIdx.x, qb = blockIdx.y;
+    if (p.causal && kb > qb) return;  // whole tile above the diagonal: never read downstream
+    const long base = (long)(bh / p.heads) * p.stride_b + (long)(bh % p.heads) * p.stride_h;
+    const uint32_t ldb = (uint32_t)p.stride_n * 2;
+    const uint32_t bytes = (uint32_t)(((long)(p.n - 1) * p.stride_n + p.d) * 2);
+    const auto rK = make_rsrc(p.K + base, bytes), rQ = make_rsrc(p.Q + base, bytes);
+    const auto rV = make_rsrc(MODE == kBackward ? p.V + base : p.K + base, bytes);
+    const auto rG = make_rsrc(MODE == kBackward ? p.dO + base : p.Q + base, bytes);
+    const int k0 = kb * 128, q0 = qb * 128;
+
+    f32x16 s[2][2], dp[2][2];
+    zero_acc(s);
+    if (MODE == kBackward) zero_acc(dp);
+
+    BufTile<BK, 128> tk, tq, tv, tg;
+    auto fetch = [&](int c0) {
+        tk.fetch(rK, k0, c0, ldb, tid);
+        tq.fetch(rQ, q0, c0, ldb, tid);
+        if (MODE == kBackward) {
+            tv.fetch(rV, k0, c0, ldb, tid);
+            tg.fetch(rG, q0, c0, ldb, tid);
+        }
+    };
+    auto commit = [&](int stage) {
+        char* b = smem + stage * kOps * kTile;
+        tk.store(b, tid);
+        tq.store(b + kTile, tid);
+        if (MODE == kBackward) {
+            tv.store(b + 2 * kTile, tid);
+            tg.store(b + 3 * kTile, tid);
+        }
+    };
+    const int chunks = p.d / BK;
+    fetch(0);
+    commit(0);
+    __syncthreads();
+    for (int kc = 0; kc < chunks; ++kc) {
+        if (kc + 1 < chunks) fetch((kc + 1) * BK);
+        const char* b = smem + (kc & 1) * kOps * kTile;
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            bf16x8 a[2], q[2];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                a[t] = load_frag<BK>(b, 64 * wm + 32 * t, ks, lane);
+                q[t] = load_frag<BK>(b + kTile, 64 * wn + 32 * t, ks, lane);
+            }
+#pragma unroll
+            for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < 2; ++tn) s[tm][tn] = mfma32(a[tm], q[tn], s[tm][tn]);
+            if (MODE == kBackward) {
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    a[t] = load_frag<BK>(b + 2 * kTile, 64 * wm + 32 * t, ks, lane);
+                    q[t] = load_frag<BK>(b + 3 * kTile, 64 * wn + 32 * t, ks, lane);
+                }
+#pragma unroll
+                for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+                    for (int tn = 0; tn < 2; ++tn) dp[tm][tn] = mfma32(a[tm], q[tn], dp[tm][tn]);
+            }
+        }
+        if (kc + 1 < chunks) commit((kc + 1) & 1);
+        __syncthreads();
+    }
+
+    // epilogue
+    const float c = p.scale * kLog2e;
+    const bool need_mask = (p.causal && kb == qb) || (k0 + 128 > p.n);
+#pragma unroll
+    for (int tn = 0; tn < 2; ++tn) {
+        const int q = q0 + 64 * wn + 32 * tn + l32;
+        const bool q_ok = q < p.n;
+        if (MODE == kStats) {
+            float x[2][16];
+            float mx = -__builtin_inff();
+#pragma unroll
+            for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    float v = s[tm][tn][i] * c;
+                    const int key = k0 + 64 * wm + 32 * tm + acc_row(i, h);
+                    if (need_mask && (key >= p.n || (p.causal && key > q))) v = -__builtin_inff();
+                    x[tm][i] = v;
+                    mx = fmaxf(mx, v);
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float m_use = mx == -__builtin_inff() ? 0.f : mx;
+            float sum = 0.f;
+#pragma unroll
+            for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(x[tm][i] - m_use);
+            sum += __shfl_xor(sum, 32, 64);
+            if (q_ok && h == 0) {
+                const long o = ((long)bh * p.n + q) * (2 * nb) + 2 * kb + wm;
+                p.stat_m[o] = mx;
+                p.stat_l[o] = sum;
+            }
+        } else {
+            const float lse2 = q_ok ? (MODE == kBackward ? p.LSE : p.LSEout)[(long)bh * p.n + q] * kLog2e
+                                    : __builtin_inff();
+            const float dl = (MODE == kBackward && q_ok) ? p.delta[(long)bh * p.n + q] : 0.f;
+            __bf16* prow = p.P + ((long)bh * p.npad + q) * p.npad;
+            __bf16* drow = p.dS + ((long)bh * p.npad + q) * p.npad;
+#pragma unroll
+            for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int key = k0 + 64 * wm + 32 * tm + 8 * g + 4 * h;
+                    float pv[4], dv[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        float v = __builtin_amdgcn_exp2f(s[tm][tn][4 * g + r] * c - lse2);
+                        // a fully masked row has LSE = -inf: exp2(+inf) must not leak out
+                        if (lse2 == -__builtin_inff()) v = 0.f;
+                        if (need_mask && (key + r >= p.n || (p.causal && key + r > q))) v = 0.f;
+                        pv[r] = v;
+                        if (MODE == kBackward) dv[r] = v * (dp[tm][tn][4 * g + r] - dl);
+                    }
+                    u32x2 a;
+                    a[0] = pack_bf16(pv[0], pv[1]);
+                    a[1] = pack_bf16(pv[2], pv[3]);
+                    *reinterpret_cast<u32x2*>(prow + key) = a;
+                    if (MODE == kBackward) {
+                        a[0] = pack_bf16(dv[0], dv[1]);
+                        a[1] = pack_bf16(dv[2], dv[3]);
+                        *reinterpret_cast<u32x2*>(drow + key) = a;
+                    }
+                }
+        }
+    }
+}
+
+// LSE from the per-chunk statistics: one thread per row.
+__global__ void __launch_bounds__(kThreads) ld_lse_combine_kernel(LargeDParams p) {
+    const long r = (long)blockIdx.x * kThreads + threadIdx.x;
+    if (r >= (long)p.batch * p.heads * p.n) return;
+    const int q = (int)(r % p.n);
+    const int nb = p.npad / 128;
+    const int chunks = 2 * (p.causal ? q / 128 + 1 : nb);
+    const float* m = p.stat_m + r * (2 * nb);
+    const float* l = p.stat_l + r * (2 * nb);
+    float M = -__builtin_inff();
+    for (int c = 0; c < chunks; ++c) M = fmaxf(M, m[c]);
+    float L = 0.f;
+    if (M != -__builtin_inff())
+        for (int c = 0; c < chunks; ++c)
+            if (m[c] != -__builtin_inff()) L += l[c] * __builtin_amdgcn_exp2f(m[c] - M);
+    p.LSEout[r] = L > 0.f ? (M + __builtin_amdgcn_logf(L)) * kLn2 : -__builtin_inff();
+}
+
+// C[m][n] = alpha * sum_k A(m, k) B(k, n): 128 x 128 output tile per workgroup, k-loop over the
+// sequence.  A is one of the n x n matrices in the workspace (row pitch npad): read as stored
+// ([m][k], A_KMAJOR = false: dQ = dS K, O = P V) or transposed ([k][m], A_KMAJOR = true:
+// dV = P^T dO, dK = dS^T Q).  B is an [n, d] tensor, k along its rows.  Under the causal rule
+// the k-range of a tile shrinks to the blocks the scores kernel wrote.
+struct GemmArgs {
+    const __bf16* A;  // workspace matrix, [bh][npad][npad]
+    const __bf16* B;  // [b, h, n, d] tensor
+    __bf16* C;        // [b, h, n, d] tensor
+    float alpha;
+};
+
+template <bool A_KMAJOR>
+__global__ void __launch_bounds__(kThreads, 2) ld_gemm_kernel(LargeDParams p, GemmArgs g) {
+    constexpr int BK = 64;
+    constexpr int kTile = 128 * BK * 2;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, h = lane >> 5, l32 = lane & 31;
+    const int wm = w >> 1, wn = w & 1;
+    const int bh = blockIdx.z, mb = blockIdx.y, n0 = blockIdx.x * 128, m0 = mb * 128;
+    const long base = (long)(bh / p.heads) * p.stride_b + (long)(bh % p.heads) * p.stride_h;
+    const auto rA = make_rsrc(g.A + (long)bh * p.npad * p.npad, (uint32_t)((long)p.npad * p.npad * 2));
+    const auto rB = make_rsrc(g.B + base, (uint32_t)(((long)(p.n - 1) * p.stride_n + p.d) * 2));
+    const uint32_t lda = (uint32_t)p.npad * 2, ldb = (uint32_t)p.stride_n * 2;
+    int k_begin = 0, k_end = p.npad;
+    if (p.causal) {
+        if (A_KMAJOR) k_begin = m0;   // queries at or after this key block
+        else k_end = m0 + 128;        // keys at or before this query block
+    }
+
+    f32x16 c[2][2];
+    zero_acc(c);
+    BufTile<A_KMAJOR ? 128 : BK, A_KMAJOR ? BK : 128> ta;
+    BufTile<128, BK> tb;
+    auto fetch = [&](int k) {
+        if (A_KMAJOR) ta.fetch(rA, k, m0, lda, tid);
+        else ta.fetch(rA, m0, k, lda, tid);
+        tb.fetch(rB, k, n0, ldb, tid);
+    };
+    auto commit = [&](int stage) {
+        ta.store(smem + stage * 2 * kTile, tid);
+        tb.store(smem + stage * 2 * kTile + kTile, tid);
+    };
+    fetch(k_begin);
+    commit(0);
+    __syncthreads();
+    int stage = 0;
+    for (int k = k_begin; k < k_end; k += BK, stage ^= 1) {
+        if (k + BK < k_end) fetch(k + BK);
+        const char* at = smem + stage * 2 * kTile;
+        const char* bt = at + kTile;
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            bf16x8 a[2], b[2];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                a[t] = A_KMAJOR ? load_frag_t<128>(at, 64 * wm + 32 * t, 16 * ks, lane)
+                                : load_frag_perm<BK>(at, 64 * wm + 32 * t, ks, lane);
+                b[t] = load_frag_t<128>(bt, 64 * wn + 32 * t, 16 * ks, lane);
+            }
+#pragma unroll
+            for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < 2; ++tn) c[tm][tn] = mfma32(a[tm], b[tn], c[tm][tn]);
+        }
+        if (k + BK < k_end) commit(stage ^ 1);
+        __syncthreads();
+    }
+    // accumulator: lane <-> output column, register <-> output row
+#pragma unroll
+    for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < 2; ++tn) {
+            const int col = n0 + 64 * wn + 32 * tn + l32;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int row = m0 + 64 * wm + 32 * tm + acc_row(i, h);
+                if (row < p.n && col < p.d) g.C[base + (long)row * p.stride_n + col] = (__bf16)(c[tm][tn][i] * g.alpha);
+            }
+        }
+}
+
+static hipError_t set_lds(const void* fn, int bytes) {
+    return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
+
+template <bool A_KMAJOR>
+static void run_gemm(const LargeDParams& p, const __bf16* A, const __bf16* B, __bf16* C, float alpha,
+                     hipStream_t stream) {
+    const dim3 grid((unsigned)((p.d + 127) / 128), (unsigned)(p.npad / 128), (unsigned)(p.batch * p.heads));
+    GemmArgs g{A, B, C, alpha};
+    hipLaunchKernelGGL(ld_gemm_kernel<A_KMAJOR>, grid, dim3(kThreads), 2 * 2 * 128 * 64 * 2, stream, p, g);
+}
+
+hipError_t launch_larged(bool backward, const LargeDParams& p, hipStream_t stream) {
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = set_lds(reinterpret_cast<const void*>(ld_scores_kernel<kStats>), 2 * 2 * 128 * 32 * 2);
+        if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_scores_kernel<kProbs>), 2 * 2 * 128 * 32 * 2);
+        if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_scores_kernel<kBackward>), 2 * 4 * 128 * 32 * 2);
+        if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_gemm_kernel<true>), 2 * 2 * 128 * 64 * 2);
+        if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_gemm_kernel<false>), 2 * 2 * 128 * 64 * 2);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const unsigned nb = (unsigned)(p.npad / 128), bh = (unsigned)(p.batch * p.heads);
+    const dim3 sgrid(nb, nb, bh), block(kThreads);
+    if (!backward) {
+        hipLaunchKernelGGL(ld_scores_kernel<kStats>, sgrid, block, 2 * 2 * 128 * 32 * 2, stream, p);
+        const long rows = (long)bh * p.n;
+        hipLaunchKernelGGL(ld_lse_combine_kernel, dim3((unsigned)((rows + kThreads - 1) / kThreads)), block, 0, stream, p);
+        hipLaunchKernelGGL(ld_scores_kernel<kProbs>, sgrid, block, 2 * 2 * 128 * 32 * 2, stream, p);
+        run_gemm<false>(p, p.P, p.V, p.Oout, 1.f, stream);
+    } else {
+        hipLaunchKernelGGL(ld_scores_kernel<kBackward>, sgrid, block, 2 * 4 * 128 * 32 * 2, stream, p);
+        run_gemm<true>(p, p.P, p.dO, p.dV, 1.f, stream);
+        run_gemm<true>(p, p.dS, p.Q, p.dK, p.scale, stream);
+        run_gemm<false>(p, p.dS, p.K, p.dQ, p.scale, stream);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace attn

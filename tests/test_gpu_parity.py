@@ -37,6 +37,12 @@ CASES = [
     W("bf16_d512", 51, 1, 2, 384, 512, "bf16"),
     W("bf16_d512_ragged_causal", 52, 1, 1, 200, 512, "bf16", causal=True),
     W("bf16_d256", 53, 1, 2, 256, 256, "bf16"),
+    W("bf16_d512_causal_5blocks", 54, 1, 2, 640, 512, "bf16", causal=True, dO_std=0.1),
+    W("bf16_d256_ragged_causal", 55, 2, 1, 333, 256, "bf16", causal=True),
+    # shapes only the generic fp32-FMA kernels take: bf16 with d outside {64,128,256,512},
+    # d = 512 under a block mask, and a block edge other than 128
+    W("bf16_d96_generic", 56, 1, 2, 150, 96, "bf16", causal=True),
+    W("bf16_d512_sparse_generic", 57, 1, 1, 256, 512, "bf16", sparse=True, block=64, extra_frac=0.4),
 ]
 
 

@@ -46,7 +46,7 @@ P = 0x1000  # a non-null, 16-byte aligned fake device address: never dereference
 
 
 def call_fwd(d, mask=None, ptrs=(P, P, P, P, P)):
-    return attn.lib().attn_fwd(ctypes.byref(d) if d is not None else None, mask, *ptrs, None)
+    return attn.lib().attn_fwd(ctypes.byref(d) if d is not None else None, mask, *ptrs, P, 1 << 40, None)
 
 
 def call_bwd(d, ptrs=(P,) * 9, ws=P, ws_bytes=1 << 30):
