@@ -40,7 +40,7 @@ __global__ void __launch_bounds__(kThreads) delta_kernel(FusedParams p, int d) {
 //   dV_w^T += dO_T^T P,   dK_w^T += Q_T^T dS         accumulators are B operands as they stand;
 //                                                    Q^T / dO^T come from transposed LDS reads
 template <int D>
-__global__ void __launch_bounds__(kThreads, 1) bwd_dkdv_kernel(FusedParams p) {
+__global__ void __launch_bounds__(kThreads, D == 64 ? 2 : 1) bwd_dkdv_kernel(FusedParams p) {
     constexpr int BR = 64, BC = 128, KS = D / 16, MT = D / 32;
     constexpr int kTileBytes = BR * D * 2;
     constexpr int kStageBytes = 2 * kTileBytes + 2 * BR * 4;
@@ -210,6 +210,166 @@ __global__ void __launch_bounds__(kThreads, 1) bwd_dkdv_kernel(FusedParams p) {
     }
 }
 
+// --------------------------------------------------------------- dK, dV, d = 128 variant
+// At d = 128 the layout above needs more than 256 registers per lane, which would leave one
+// wave per SIMD and nothing to hide latency behind.  This variant keeps two workgroups per CU:
+// a workgroup owns 64 keys and splits each (64 query x 64 key) tile twice over its 4 waves,
+//   phase 1: wave (wk, wx) computes S and dP for query half wx and key half wk, then P and dS
+//            go to LDS as bf16 tiles [key][query];
+//   phase 2: wave (wk, wx) accumulates the d-half wx of dV^T and dK^T for key half wk over all
+//            64 queries, reading P / dS back as B operands and dO^T / Q^T transposed.
+// lse2 / delta of a query half live one row per lane and are fetched by lane shuffles.
+template <int D>
+__global__ void __launch_bounds__(kThreads, 2) bwd_dkdv_split_kernel(FusedParams p) {
+    constexpr int BR = 64, BC = 64, KS = D / 16, MH = D / 64;  // MH m-tiles per d-half
+    constexpr int kTileBytes = BR * D * 2;
+    constexpr int kStageBytes = 2 * kTileBytes;
+    constexpr int kPBytes = BC * BR * 2;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    char* const p_lds = smem + 2 * kStageBytes;
+    char* const ds_lds = p_lds + kPBytes;
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, h = lane >> 5, l32 = lane & 31;
+    const int wk = w & 1, wx = w >> 1;
+    const int key_blocks = (p.n + BC - 1) / BC;
+    int bh, j;
+    decode_block(blockIdx.x, key_blocks, p.batch * p.heads, bh, j);
+    const long base = (long)(bh / p.heads) * p.stride_b + (long)(bh % p.heads) * p.stride_h;
+    const long ld = p.stride_n;
+    const int j0 = j * BC;
+    const float* lse_g = p.LSE + (long)bh * p.n;
+    const float* delta_g = p.delta + (long)bh * p.n;
+
+    int n_it, t0 = 0, lp0 = 0;
+    if (p.list_ptr) {
+        lp0 = p.list_ptr[j0 / 128];
+        n_it = (p.list_ptr[j0 / 128 + 1] - lp0) * (128 / BR);
+    } else {
+        t0 = p.causal ? j0 / BR : 0;
+        n_it = (p.n + BR - 1) / BR - t0;
+    }
+    auto tile_start = [&](int it) -> int { return tile_start_row<BR>(p.list_idx, lp0, t0, it); };
+
+    const int key = j0 + 32 * wk + l32;
+    bf16x8 kf[KS], vf[KS];
+    {
+        const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            kf[ks] = zero;
+            vf[ks] = zero;
+            if (key < p.n) {
+                kf[ks] = *reinterpret_cast<const bf16x8*>(p.K + base + (long)key * ld + 16 * ks + 8 * h);
+                vf[ks] = *reinterpret_cast<const bf16x8*>(p.V + base + (long)key * ld + 16 * ks + 8 * h);
+            }
+        }
+    }
+    f32x16 dk[MH], dv[MH];
+#pragma unroll
+    for (int m = 0; m < MH; ++m)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { dk[m][i] = 0.f; dv[m][i] = 0.f; }
+
+    const float c = p.scale * kLog2e;
+    // Row i0 + 32 wx + l32 of the tile being fetched.  The loaded values are not touched until
+    // the next iteration, so nothing waits on the copies in flight behind them.
+    float lse_raw = 0.f, delta_raw = 0.f;
+    bool row_ok = false;
+    auto fetch = [&](int i0, int stage) {
+        char* s = smem + stage * kStageBytes;
+        load_tile_direct<D, BR>(p.Q + base, ld, i0, p.n, s, tid);
+        load_tile_direct<D, BR>(p.dO + base, ld, i0, p.n, s + kTileBytes, tid);
+        const int q = i0 + 32 * wx + l32;
+        row_ok = q < p.n;
+        lse_raw = lse_g[min(q, p.n - 1)];
+        delta_raw = delta_g[min(q, p.n - 1)];
+    };
+    int i0_next = n_it > 0 ? tile_start(0) : 0;
+    if (n_it > 0) fetch(i0_next, 0);
+    wait_direct_loads();
+    __syncthreads();
+
+    for (int it = 0; it < n_it; ++it) {
+        const int i0 = i0_next;
+        const bool more = it + 1 < n_it;
+        if (more) i0_next = tile_start(it + 1);
+        const float lse_cur = row_ok ? lse_raw * kLog2e : __builtin_inff();
+        const float delta_cur = row_ok ? delta_raw : 0.f;
+        if (more) fetch(i0_next, (it + 1) & 1);  // that stage was last read before barrier B
+        const char* qs = smem + (it & 1) * kStageBytes;
+        const char* dos = qs + kTileBytes;
+        const bool skip = p.causal && (i0 + BR - 1 < j0);  // uniform over the workgroup
+
+        if (!skip) {
+            // ---- phase 1: S, dP for (query half wx) x (key half wk)
+            f32x16 s, dp;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) s = mfma32(load_frag<D>(qs, 32 * wx, ks, lane), kf[ks], s);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) dp = mfma32(load_frag<D>(dos, 32 * wx, ks, lane), vf[ks], dp);
+            const bool need_mask = p.causal && (i0 < j0 + BC - 1);
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                float pv[4], dsv[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int i = 4 * g + r, row = 8 * g + 4 * h + r;
+                    const float L = __shfl(lse_cur, row, 64), Dl = __shfl(delta_cur, row, 64);
+                    float v = __builtin_amdgcn_exp2f(s[i] * c - L);
+                    if (need_mask && key > i0 + 32 * wx + row) v = 0.f;
+                    pv[r] = v;
+                    dsv[r] = v * (dp[i] - Dl);
+                }
+                // [key][query] tiles: four consecutive queries of this lane's key
+                const int off = tile_off<BR>(32 * wk + l32, 4 * wx + g) + 8 * h;
+                u32x2 a, b;
+                a[0] = pack_bf16(pv[0], pv[1]);
+                a[1] = pack_bf16(pv[2], pv[3]);
+                b[0] = pack_bf16(dsv[0], dsv[1]);
+                b[1] = pack_bf16(dsv[2], dsv[3]);
+                *reinterpret_cast<u32x2*>(p_lds + off) = a;
+                *reinterpret_cast<u32x2*>(ds_lds + off) = b;
+            }
+        }
+        lds_barrier();  // P, dS visible; the tile copies for the next iteration stay in flight
+        if (!skip) {
+            // ---- phase 2: d-half wx of dV^T, dK^T for key half wk over the 64 queries
+#pragma unroll
+            for (int ks = 0; ks < BR / 16; ++ks) {
+                const bf16x8 bp = load_frag_perm<BR>(p_lds, 32 * wk, ks, lane);
+                const bf16x8 bs = load_frag_perm<BR>(ds_lds, 32 * wk, ks, lane);
+#pragma unroll
+                for (int m = 0; m < MH; ++m) {
+                    dv[m] = mfma32(load_frag_t<D>(dos, 32 * (MH * wx + m), 16 * ks, lane), bp, dv[m]);
+                    dk[m] = mfma32(load_frag_t<D>(qs, 32 * (MH * wx + m), 16 * ks, lane), bs, dk[m]);
+                }
+            }
+        }
+        wait_direct_loads();
+        __syncthreads();
+    }
+
+    if (key < p.n) {
+        __bf16* dk_row = p.dK + base + (long)key * ld;
+        __bf16* dv_row = p.dV + base + (long)key * ld;
+#pragma unroll
+        for (int m = 0; m < MH; ++m)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int col = 32 * (MH * wx + m) + 8 * g + 4 * h;
+                u32x2 a, b;
+                a[0] = pack_bf16(dk[m][4 * g + 0] * p.scale, dk[m][4 * g + 1] * p.scale);
+                a[1] = pack_bf16(dk[m][4 * g + 2] * p.scale, dk[m][4 * g + 3] * p.scale);
+                b[0] = pack_bf16(dv[m][4 * g + 0], dv[m][4 * g + 1]);
+                b[1] = pack_bf16(dv[m][4 * g + 2], dv[m][4 * g + 3]);
+                *reinterpret_cast<u32x2*>(dk_row + col) = a;
+                *reinterpret_cast<u32x2*>(dv_row + col) = b;
+            }
+    }
+}
+
 // ----------------------------------------------------------------------------------- dQ
 // Wave w owns queries i0 + 32w .. +31: their Q and dO rows stay in registers as B operands.
 // Per key tile (64 keys, two halves T):
@@ -217,7 +377,7 @@ __global__ void __launch_bounds__(kThreads, 1) bwd_dkdv_kernel(FusedParams p) {
 //   dS^T = P^T (dP^T - delta)                        per-lane scalars lse2, delta
 //   dQ_w^T += K_T^T dS^T                             K^T from transposed LDS reads
 template <int D>
-__global__ void __launch_bounds__(kThreads, 1) bwd_dq_kernel(FusedParams p) {
+__global__ void __launch_bounds__(kThreads, 2) bwd_dq_kernel(FusedParams p) {
     constexpr int BR = 128, BC = 64, KS = D / 16, MT = D / 32;
     constexpr int kTileBytes = BC * D * 2;
     constexpr int kStageBytes = 2 * kTileBytes;
@@ -296,44 +456,35 @@ __global__ void __launch_bounds__(kThreads, 1) bwd_dq_kernel(FusedParams p) {
         // causal: this wave's last query precedes the tile's first key -> nothing visible
         const bool skip = p.causal && (i0 + 32 * w + 31 < j0);
         if (!skip) {
-            f32x16 st[2], dpt[2];
-#pragma unroll
-            for (int T = 0; T < 2; ++T)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) { st[T][i] = 0.f; dpt[T][i] = 0.f; }
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-                for (int T = 0; T < 2; ++T) st[T] = mfma32(load_frag<D>(ks_t, 32 * T, ks, lane), qf[ks], st[T]);
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-                for (int T = 0; T < 2; ++T) dpt[T] = mfma32(load_frag<D>(vs_t, 32 * T, ks, lane), gf[ks], dpt[T]);
-
             const bool need_mask = (p.causal && (j0 + BC - 1 > i0 + 32 * w)) || (j0 + BC > p.n);
+            // the two 32-key halves one after the other: half the score registers live at a time
 #pragma unroll
-            for (int T = 0; T < 2; ++T)
+            for (int T = 0; T < 2; ++T) {
+                f32x16 st, dpt;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) { st[i] = 0.f; dpt[i] = 0.f; }
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) st = mfma32(load_frag<D>(ks_t, 32 * T, ks, lane), qf[ks], st);
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) dpt = mfma32(load_frag<D>(vs_t, 32 * T, ks, lane), gf[ks], dpt);
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    float pv = __builtin_amdgcn_exp2f(st[T][i] * c - lse2);
+                    float pv = __builtin_amdgcn_exp2f(st[i] * c - lse2);
                     if (need_mask) {
                         const int key = j0 + 32 * T + acc_row(i, h);
                         if (key >= p.n || (p.causal && key > q)) pv = 0.f;
                     }
-                    dpt[T][i] = pv * (dpt[T][i] - dl);
+                    dpt[i] = pv * (dpt[i] - dl);
                 }
-            bf16x8 dsb[2][2];
+                bf16x8 dsb[2];
 #pragma unroll
-            for (int T = 0; T < 2; ++T)
+                for (int ss = 0; ss < 2; ++ss) dsb[ss] = acc_to_operand(dpt, ss);
 #pragma unroll
-                for (int ss = 0; ss < 2; ++ss) dsb[T][ss] = acc_to_operand(dpt[T], ss);
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                for (int T = 0; T < 2; ++T)
+                for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                     for (int ss = 0; ss < 2; ++ss)
-                        dq[mt] = mfma32(load_frag_t<D>(ks_t, 32 * mt, 32 * T + 16 * ss, lane), dsb[T][ss], dq[mt]);
+                        dq[mt] = mfma32(load_frag_t<D>(ks_t, 32 * mt, 32 * T + 16 * ss, lane), dsb[ss], dq[mt]);
+            }
         }
         if (more) commit((it + 1) & 1);
         __syncthreads();
@@ -365,12 +516,14 @@ static hipError_t launch_bwd(const FusedParams& p, const int32_t* csr_ptr, const
     const int bh = p.batch * p.heads;
     launch_delta(p, D, stream);
 
-    constexpr int kv_lds = 2 * (2 * 64 * D * 2 + 2 * 64 * 4);
+    constexpr bool kSplit = D == 128;
+    constexpr int kv_lds = kSplit ? 2 * (2 * 64 * D * 2) + 2 * 64 * 64 * 2 : 2 * (2 * 64 * D * 2 + 2 * 64 * 4);
     constexpr int q_lds = 2 * (2 * 64 * D * 2);
+    const void* kv_fn = kSplit ? reinterpret_cast<const void*>(bwd_dkdv_split_kernel<D>)
+                               : reinterpret_cast<const void*>(bwd_dkdv_kernel<D>);
     static bool configured = false;
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dkdv_kernel<D>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kv_lds);
+        hipError_t e = hipFuncSetAttribute(kv_fn, hipFuncAttributeMaxDynamicSharedMemorySize, kv_lds);
         if (e != hipSuccess) return e;
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dq_kernel<D>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, q_lds);
@@ -381,7 +534,11 @@ static hipError_t launch_bwd(const FusedParams& p, const int32_t* csr_ptr, const
     FusedParams pk = p;
     pk.list_ptr = csc_ptr;
     pk.list_idx = csc_idx;
-    hipLaunchKernelGGL(bwd_dkdv_kernel<D>, dim3((unsigned)(blocks128 * bh)), dim3(kThreads), kv_lds, stream, pk);
+    if (kSplit)
+        hipLaunchKernelGGL(bwd_dkdv_split_kernel<D>, dim3((unsigned)((p.n + 63) / 64 * bh)), dim3(kThreads), kv_lds,
+                           stream, pk);
+    else
+        hipLaunchKernelGGL(bwd_dkdv_kernel<D>, dim3((unsigned)(blocks128 * bh)), dim3(kThreads), kv_lds, stream, pk);
     FusedParams pq = p;
     pq.list_ptr = csr_ptr;
     pq.list_idx = csr_idx;

@@ -100,6 +100,18 @@ __device__ __forceinline__ bf16x8 load_frag_t(const char* tile, int col0, int ro
     return __builtin_bit_cast(bf16x8, r);
 }
 
+// Operand whose k index runs along the tile's contiguous dimension, but with the k order of
+// load_frag_t (element t of half h <-> column 16 ks + 8 (t / 4) + 4h + t % 4), for products
+// whose other operand is read transposed.
+template <int D>
+__device__ __forceinline__ bf16x8 load_frag_perm(const char* tile, int row0, int ks, int lane) {
+    const int row = row0 + (lane & 31), h = lane >> 5;
+    const u32x2 lo = *reinterpret_cast<const u32x2*>(tile + tile_off<D>(row, 2 * ks) + 8 * h);
+    const u32x2 hi = *reinterpret_cast<const u32x2*>(tile + tile_off<D>(row, 2 * ks + 1) + 8 * h);
+    u32x4 r = {lo[0], lo[1], hi[0], hi[1]};
+    return __builtin_bit_cast(bf16x8, r);
+}
+
 // Cooperative copy of a [ROWS x D] bf16 tile: global (row stride `ld` elements) -> registers
 // -> swizzled LDS tile.  Rows at or beyond `rows_valid` read as zero.
 template <int D, int ROWS>
@@ -129,6 +141,48 @@ struct TileCopy {
         }
     }
 };
+
+// Asynchronous copy of a [ROWS x D] bf16 tile from global memory straight into a swizzled LDS
+// tile (global_load_lds_dwordx4: no staging registers).  One instruction moves 1 KB per wave and
+// lands lane l's 16 bytes at LDS base + 16 l, so the lane that owns LDS position (row, chunk p)
+// fetches global chunk p ^ swz(row): the swizzle is applied on the global side.  Rows at or
+// beyond rows_valid re-read the last valid row (finite values that the callers mask out).
+// The copy is complete for the issuing wave after wait_direct_loads().
+template <int D, int ROWS>
+__device__ __forceinline__ void load_tile_direct(const __bf16* base, long ld, int row_begin, int rows_valid,
+                                                 char* tile, int tid) {
+    constexpr int kRowsPerInst = 1024 / (D * 2);
+    constexpr int kInst = ROWS / (4 * kRowsPerInst);
+    static_assert(ROWS % (4 * kRowsPerInst) == 0, "tile must split evenly over four waves");
+    const int lane = tid & 63, w = tid >> 6;
+#pragma unroll
+    for (int u = 0; u < kInst; ++u) {
+        const int row = (u * 4 + w) * kRowsPerInst + lane / (D / 8);
+        const int c = (lane % (D / 8)) ^ swz<D>(row);
+        const int grow = min(row_begin + row, rows_valid - 1);
+        __builtin_amdgcn_global_load_lds(
+            (const void __attribute__((address_space(1)))*)(base + (long)grow * ld + c * 8),
+            (void ATTN_LDS*)(tile + (u * 4 + w) * 1024), 16, 0, 0);
+    }
+}
+__device__ __forceinline__ void wait_direct_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// Workgroup barrier that orders LDS traffic only: it waits for this wave's LDS operations but
+// not for global loads still in flight (__syncthreads would also drain those).
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// Start row of streamed tile `it` of a workgroup: dense tiles follow one another from t0;
+// under a block mask, entry it / sub of the block list picks a 128-row block and it % sub the
+// tile inside it.  The list read is forced onto the scalar unit (all values are uniform).
+template <int TILE>
+__device__ __forceinline__ int tile_start_row(const int32_t* list_idx, int lp0, int t0, int it) {
+    constexpr int kSub = 128 / TILE;
+    if (list_idx) {
+        const int e = __builtin_amdgcn_readfirstlane(lp0 + it / kSub);
+        return list_idx[e] * 128 + (it % kSub) * TILE;
+    }
+    return (t0 + it) * TILE;
+}
 
 // Head and tile decoding shared by the kernels.  Workgroups are handed to the 8 XCDs round
 // robin by linear id, so ids congruent mod 8 share an L2: all tiles of one (batch, head) are

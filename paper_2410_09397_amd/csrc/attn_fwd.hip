@@ -14,7 +14,7 @@ namespace attn {
 //            see the same maximum; their partial sums are added at the end)
 //   O_w^T += V_T^T P^T                 V^T from transposed LDS reads, P^T straight from registers
 template <int D>
-__global__ void __launch_bounds__(kThreads, 1) fwd_kernel(FusedParams p) {
+__global__ void __launch_bounds__(kThreads, 2) fwd_kernel(FusedParams p) {
     constexpr int BR = 128, BC = 64, KS = D / 16, MT = D / 32;
     constexpr int kTileBytes = BC * D * 2;
     constexpr int kStageBytes = 2 * kTileBytes;

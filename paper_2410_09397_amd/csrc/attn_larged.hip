@@ -49,18 +49,6 @@ struct BufTile {
     }
 };
 
-// Operand whose k index runs along the tile's contiguous dimension, but with the k order of
-// load_frag_t (element t of half h <-> column 16 ks + 8 (t / 4) + 4h + t % 4), for products
-// whose other operand is read transposed.
-template <int D>
-__device__ __forceinline__ bf16x8 load_frag_perm(const char* tile, int row0, int ks, int lane) {
-    const int row = row0 + (lane & 31), h = lane >> 5;
-    const u32x2 lo = *reinterpret_cast<const u32x2*>(tile + tile_off<D>(row, 2 * ks) + 8 * h);
-    const u32x2 hi = *reinterpret_cast<const u32x2*>(tile + tile_off<D>(row, 2 * ks + 1) + 8 * h);
-    u32x4 r = {lo[0], lo[1], hi[0], hi[1]};
-    return __builtin_bit_cast(bf16x8, r);
-}
-
 __device__ __forceinline__ void zero_acc(f32x16 (&c)[2][2]) {
 #pragma unroll
     for (int a = 0; a < 2; ++a)
