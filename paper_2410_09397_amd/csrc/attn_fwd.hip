@@ -37,10 +37,7 @@ __global__ void __launch_bounds__(kThreads, 2) fwd_kernel(FusedParams p) {
         const int k_end = p.causal ? min(p.n, i0 + BR) : p.n;
         n_it = (k_end + BC - 1) / BC;
     }
-    auto tile_start = [&](int it) -> int {
-        if (p.list_ptr) return p.list_idx[lp0 + it / (128 / BC)] * 128 + (it % (128 / BC)) * BC;
-        return it * BC;
-    };
+    auto tile_start = [&](int it) -> int { return tile_start_row<BC>(p.list_idx, lp0, 0, it); };
 
     const int q = i0 + 32 * w + l32;
     const bool q_ok = q < p.n;
@@ -63,26 +60,25 @@ __global__ void __launch_bounds__(kThreads, 2) fwd_kernel(FusedParams p) {
     float l_run = 0.f;                // this lane's share of sum exp2(c s - m_run)
 
     const float c = p.scale * kLog2e;
-    TileCopy<D, BC> ck, cv;
-    auto fetch = [&](int j0) {
-        ck.fetch(p.K + base, ld, j0, p.n, tid);
-        cv.fetch(p.V + base, ld, j0, p.n, tid);
-    };
-    auto commit = [&](int stage) {
+    // K and V tiles go straight from global memory into the LDS stage that was last read one
+    // iteration ago; rows past n repeat the last row and are masked below.
+    auto fetch = [&](int j0, int stage) {
         char* s = smem + stage * kStageBytes;
-        ck.store(s, tid);
-        cv.store(s + kTileBytes, tid);
+        load_tile_direct<D, BC>(p.K + base, ld, j0, p.n, s, tid);
+        load_tile_direct<D, BC>(p.V + base, ld, j0, p.n, s + kTileBytes, tid);
     };
-    if (n_it > 0) {
-        fetch(tile_start(0));
-        commit(0);
-    }
+    int j0_next = n_it > 0 ? tile_start(0) : 0;
+    if (n_it > 0) fetch(j0_next, 0);
+    wait_direct_loads();
     __syncthreads();
 
     for (int it = 0; it < n_it; ++it) {
-        const int j0 = tile_start(it);
+        const int j0 = j0_next;
         const bool more = it + 1 < n_it;
-        if (more) fetch(tile_start(it + 1));
+        if (more) {
+            j0_next = tile_start(it + 1);
+            fetch(j0_next, (it + 1) & 1);
+        }
         const char* ks_t = smem + (it & 1) * kStageBytes;
         const char* vs_t = ks_t + kTileBytes;
 
@@ -144,7 +140,7 @@ __global__ void __launch_bounds__(kThreads, 2) fwd_kernel(FusedParams p) {
                     for (int ss = 0; ss < 2; ++ss)
                         o[mt] = mfma32(load_frag_t<D>(vs_t, 32 * mt, 32 * T + 16 * ss, lane), pb[T][ss], o[mt]);
         }
-        if (more) commit((it + 1) & 1);
+        wait_direct_loads();
         __syncthreads();
     }
 
