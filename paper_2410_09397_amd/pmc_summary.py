@@ -1,0 +1,156 @@
+"""Condenses rocprofv3 output of `bench.py` into the short text summaries kept under profiles/.
+
+Inputs are the CSV files of three profiler runs of the same bench command:
+  --stats DIR   rocprofv3 --kernel-trace --stats   (per-kernel durations)
+  --fetch DIR   rocprofv3 --pmc FETCH_SIZE         (with bench.py --calibrate-copy)
+  --write DIR   rocprofv3 --pmc WRITE_SIZE         (with bench.py --calibrate-copy)
+The byte counters are scaled by what they read for the plain 1 GiB device copy that
+`--calibrate-copy` adds to the run.  Writes profiles/<kernel group>_<workload>.md and updates
+profiles/hbm_traffic.json (HBM bytes of one backward call), which bench.py reports as
+roofline.traffic.
+"""
+import argparse
+import collections
+import csv
+import glob
+import json
+import os
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+COPY_BYTES = float(1 << 30)  # bytes read, and bytes written, by the calibration copy
+BWD_KERNELS = ("delta_kernel", "bwd_dkdv", "bwd_dq", "ld_scores_kernel<2>", "ld_gemm_kernel", "generic_delta",
+               "generic_dq", "generic_dkdv")
+FWD_KERNELS = ("fwd_kernel", "ld_scores_kernel<0>", "ld_scores_kernel<1>", "ld_lse_combine", "generic_fwd")
+
+
+def _one(pattern):
+    files = glob.glob(pattern, recursive=True)
+    if not files:
+        raise FileNotFoundError(pattern)
+    return files[0]
+
+
+def short(name):
+    return name.split("(")[0].replace("void ", "").replace("attn::", "")
+
+
+def kernel_stats(d):
+    rows = {}
+    with open(_one(os.path.join(d, "**", "*kernel_stats.csv"))) as fh:
+        for r in csv.DictReader(fh):
+            rows[short(r["Name"])] = (int(r["Calls"]), float(r["AverageNs"]))
+    return rows
+
+
+COPIES = 3  # device copies that bench.py --calibrate-copy issues (the runtime may split each in several dispatches)
+
+
+def counter_avg(d, counter):
+    """Average counter value per dispatch and per kernel; for the calibration copy, per copy."""
+    acc = collections.defaultdict(list)
+    with open(_one(os.path.join(d, "**", "*counter_collection.csv"))) as fh:
+        for r in csv.DictReader(fh):
+            if r["Counter_Name"] == counter:
+                acc[short(r["Kernel_Name"])].append(float(r["Counter_Value"]))
+    return {k: (sum(v) / COPIES if "copyBuffer" in k else sum(v) / len(v)) for k, v in acc.items()}
+
+
+def per_call_weights(name, calls, base_calls):
+    """(launches per attn_bwd call, launches per attn_fwd call) of a kernel."""
+    if "ld_gemm_kernel<false>" in name:  # dQ = dS K in the backward, O = P V in the forward
+        return 1.0, 1.0
+    k = calls / float(base_calls)
+    return (k, 0.0) if is_in(name, BWD_KERNELS) else (0.0, k)
+
+
+def is_in(name, group):
+    return any(g in name for g in group)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--workload", required=True, help="workload name as printed in bench.py's config.workload")
+    ap.add_argument("--workload-index", type=int, required=True)
+    ap.add_argument("--stats", required=True)
+    ap.add_argument("--fetch", required=True)
+    ap.add_argument("--write", required=True)
+    ap.add_argument("--bench-json", default=None, help="file holding the bench.py JSON line of the stats run")
+    args = ap.parse_args()
+
+    stats = kernel_stats(args.stats)
+    fetch = counter_avg(args.fetch, "FETCH_SIZE")
+    write = counter_avg(args.write, "WRITE_SIZE")
+    copy_f = [v for k, v in fetch.items() if "copyBuffer" in k]
+    copy_w = [v for k, v in write.items() if "copyBuffer" in k]
+    if not copy_f or not copy_w:
+        raise RuntimeError("calibration copy kernel not found: run bench.py with --calibrate-copy")
+    # counters are in KiB-like units per dispatch: bytes = value * factor * 1024
+    f_r = COPY_BYTES / 1024.0 / copy_f[0]
+    f_w = COPY_BYTES / 1024.0 / copy_w[0]
+
+    lines = []
+    w = args.workload_index
+    lines.append("# rocprofv3 summary: attention kernels, workload %s\n" % args.workload)
+    lines.append("Commands (from the repository root, on one MI355X; `cd /tmp && export TMPDIR=/tmp` first):\n")
+    lines.append("```")
+    lines.append("rocprofv3 --kernel-trace --stats -d %s -o w%d --output-format csv -- python bench.py --workload %d "
+                 "--steps 5 --warmup 2 --no-cpu-baseline" % (args.stats, w, w))
+    for c, d in (("FETCH_SIZE", args.fetch), ("WRITE_SIZE", args.write)):
+        lines.append("rocprofv3 --pmc %s -d %s -o pmc --output-format csv -- python bench.py --workload %d --steps 3 "
+                     "--warmup 1 --no-cpu-baseline --calibrate-copy" % (c, d, w))
+    lines.append("python -m paper_2410_09397_amd.pmc_summary --workload %s --workload-index %d --stats %s --fetch %s "
+                 "--write %s" % (args.workload, w, args.stats, args.fetch, args.write))
+    lines.append("```\n")
+    if args.bench_json and os.path.exists(args.bench_json):
+        for l in open(args.bench_json):
+            if l.startswith("{"):
+                j = json.loads(l)
+                lines.append("bench.py line of the kernel-trace run: value %.1f %s, bwd %.3f ms, fwd %.3f ms, "
+                             "ms_per_step %.3f\n" % (j["value"], j["unit"], j["bwd_ms"], j["fwd_ms"], j["ms_per_step"]))
+    lines.append("Calibration (plain 1 GiB device copy in the same run): FETCH_SIZE reads %.1f -> factor %.3f; "
+                 "WRITE_SIZE reads %.1f -> factor %.3f (bytes = counter x factor x 1024).\n"
+                 % (copy_f[0], f_r, copy_w[0], f_w))
+    lines.append("| kernel | calls | avg duration (us) | HBM read (MB) | HBM written (MB) |")
+    lines.append("|---|---|---|---|---|")
+    tot = {"bwd": [0.0, 0.0, 0.0], "fwd": [0.0, 0.0, 0.0]}
+    base_calls = max(1, min(c for n, (c, _) in stats.items() if is_in(n, BWD_KERNELS + FWD_KERNELS)))
+    for name, (calls, avg) in sorted(stats.items(), key=lambda kv: -kv[1][1]):
+        if not (is_in(name, BWD_KERNELS) or is_in(name, FWD_KERNELS)):
+            continue
+        rd = fetch.get(name, 0.0) * f_r * 1024.0
+        wr = write.get(name, 0.0) * f_w * 1024.0
+        # a kernel launched more than once per call (the large-d GEMM) counts that many times
+        wb, wf = per_call_weights(name, calls, base_calls)
+        for grp, k in (("bwd", wb), ("fwd", wf)):
+            tot[grp][0] += avg * k
+            tot[grp][1] += rd * k
+            tot[grp][2] += wr * k
+        lines.append("| %s | %d | %.1f | %.1f | %.1f |" % (name, calls, avg / 1e3, rd / 1e6, wr / 1e6))
+    lines.append("")
+    for grp, label in (("bwd", "attn_bwd call (all its kernels)"), ("fwd", "attn_fwd call")):
+        t = tot[grp]
+        lines.append("%s: %.3f ms, HBM read %.1f MB + written %.1f MB = %.1f MB" %
+                     (label, t[0] / 1e6, t[1] / 1e6, t[2] / 1e6, (t[1] + t[2]) / 1e6))
+    from paper_2410_09397_amd import io_bound, synth
+    wl = synth.workload(w)
+    y = io_bound.yardstick(wl)
+    bwd_bytes = tot["bwd"][1] + tot["bwd"][2]
+    lines.append("\nPaper's I/O yardstick for the backward (max{compulsory, Theta-term at M = 160 KB}): %.1f MB; "
+                 "measured / yardstick = %.2f" % (y / 1e6, bwd_bytes / y))
+    lines.append("Algorithmic backward FLOPs %.4g -> %.1f TFLOP/s over the summed kernel durations (%.1f %% of the "
+                 "2500 TFLOP/s dense bf16 MFMA peak)." % (wl.bwd_flops(), wl.bwd_flops() / (tot["bwd"][0] * 1e-9) * 1e-12,
+                                                           wl.bwd_flops() / (tot["bwd"][0] * 1e-9) * 1e-12 / 25.0))
+    out_dir = os.path.join(ROOT, "profiles")
+    os.makedirs(out_dir, exist_ok=True)
+    with open(os.path.join(out_dir, "attn_kernels_%s.md" % args.workload), "w") as fh:
+        fh.write("\n".join(lines) + "\n")
+    tpath = os.path.join(out_dir, "hbm_traffic.json")
+    traffic = json.load(open(tpath)) if os.path.exists(tpath) else {}
+    traffic[args.workload] = bwd_bytes
+    with open(tpath, "w") as fh:
+        json.dump(traffic, fh, indent=1, sort_keys=True)
+    print("\n".join(lines))
+
+
+if __name__ == "__main__":
+    main()
