@@ -214,11 +214,11 @@ __global__ void __launch_bounds__(kThreads, D == 64 ? 2 : 1) bwd_dkdv_kernel(Fus
 // At d = 128 the layout above needs more than 256 registers per lane, which would leave one
 // wave per SIMD and nothing to hide latency behind.  This variant keeps two workgroups per CU:
 // a workgroup owns 64 keys and splits each (64 query x 64 key) tile twice over its 4 waves,
-//   phase 1: wave (wk, wx) computes S and dP for query half wx and key half wk, then P and dS
-//            go to LDS as bf16 tiles [key][query];
+//   phase 1: wave (wk, wx) computes S^T and dP^T for key half wk and query half wx (lane <->
+//            query), then P and dS go to LDS as bf16 tiles [query][key];
 //   phase 2: wave (wk, wx) accumulates the d-half wx of dV^T and dK^T for key half wk over all
-//            64 queries, reading P / dS back as B operands and dO^T / Q^T transposed.
-// lse2 / delta of a query half live one row per lane and are fetched by lane shuffles.
+//            64 queries; P / dS (B operands) and dO^T / Q^T (A operands) are all read with
+//            transposing LDS loads.
 template <int D>
 __global__ void __launch_bounds__(kThreads, 2) bwd_dkdv_split_kernel(FusedParams p) {
     constexpr int BR = 64, BC = 64, KS = D / 16, MH = D / 64;  // MH m-tiles per d-half
@@ -301,29 +301,30 @@ __global__ void __launch_bounds__(kThreads, 2) bwd_dkdv_split_kernel(FusedParams
         const bool skip = p.causal && (i0 + BR - 1 < j0);  // uniform over the workgroup
 
         if (!skip) {
-            // ---- phase 1: S, dP for (query half wx) x (key half wk)
+            // ---- phase 1: S^T, dP^T for (key half wk) x (query half wx); the resident K / V
+            // fragments serve as A operands, so a lane holds one query and lse2 / delta are scalars
             f32x16 s, dp;
 #pragma unroll
             for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) s = mfma32(load_frag<D>(qs, 32 * wx, ks, lane), kf[ks], s);
+            for (int ks = 0; ks < KS; ++ks) s = mfma32(kf[ks], load_frag<D>(qs, 32 * wx, ks, lane), s);
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) dp = mfma32(load_frag<D>(dos, 32 * wx, ks, lane), vf[ks], dp);
+            for (int ks = 0; ks < KS; ++ks) dp = mfma32(vf[ks], load_frag<D>(dos, 32 * wx, ks, lane), dp);
             const bool need_mask = p.causal && (i0 < j0 + BC - 1);
+            const int q = i0 + 32 * wx + l32;
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 float pv[4], dsv[4];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int i = 4 * g + r, row = 8 * g + 4 * h + r;
-                    const float L = __shfl(lse_cur, row, 64), Dl = __shfl(delta_cur, row, 64);
-                    float v = __builtin_amdgcn_exp2f(s[i] * c - L);
-                    if (need_mask && key > i0 + 32 * wx + row) v = 0.f;
+                    const int i = 4 * g + r;
+                    float v = __builtin_amdgcn_exp2f(s[i] * c - lse_cur);
+                    if (need_mask && j0 + 32 * wk + 8 * g + 4 * h + r > q) v = 0.f;
                     pv[r] = v;
-                    dsv[r] = v * (dp[i] - Dl);
+                    dsv[r] = v * (dp[i] - delta_cur);
                 }
-                // [key][query] tiles: four consecutive queries of this lane's key
-                const int off = tile_off<BR>(32 * wk + l32, 4 * wx + g) + 8 * h;
+                // [query][key] tiles: four consecutive keys of this lane's query
+                const int off = tile_off<BC>(32 * wx + l32, 4 * wk + g) + 8 * h;
                 u32x2 a, b;
                 a[0] = pack_bf16(pv[0], pv[1]);
                 a[1] = pack_bf16(pv[2], pv[3]);
@@ -338,8 +339,8 @@ __global__ void __launch_bounds__(kThreads, 2) bwd_dkdv_split_kernel(FusedParams
             // ---- phase 2: d-half wx of dV^T, dK^T for key half wk over the 64 queries
 #pragma unroll
             for (int ks = 0; ks < BR / 16; ++ks) {
-                const bf16x8 bp = load_frag_perm<BR>(p_lds, 32 * wk, ks, lane);
-                const bf16x8 bs = load_frag_perm<BR>(ds_lds, 32 * wk, ks, lane);
+                const bf16x8 bp = load_frag_t<BC>(p_lds, 32 * wk, 16 * ks, lane);
+                const bf16x8 bs = load_frag_t<BC>(ds_lds, 32 * wk, 16 * ks, lane);
 #pragma unroll
                 for (int m = 0; m < MH; ++m) {
                     dv[m] = mfma32(load_frag_t<D>(dos, 32 * (MH * wx + m), 16 * ks, lane), bp, dv[m]);
