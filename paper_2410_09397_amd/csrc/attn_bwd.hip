@@ -6,6 +6,8 @@
 // q = dO h^T, A = S A_2^T, f = exp(A) / l, p = f o q - diag(v) f, followed by the three
 // products that use f and p.  The resident operand is the owned block, so dK/dV (resp. dQ)
 // accumulate in registers with no atomics and no n x n matrix ever leaves the chip.
+#include <type_traits>
+
 #include "attn_common.hpp"
 #include "attn_internal.hpp"
 
@@ -46,7 +48,8 @@ __global__ void __launch_bounds__(kThreads, D == 64 ? 2 : 1) bwd_dkdv_kernel(Fus
     constexpr int kStageBytes = 2 * kTileBytes + 2 * BR * 4;
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, h = lane >> 5, l32 = lane & 31;
+    const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, l32 = lane & 31;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, uniform
     const int key_blocks = (p.n + BC - 1) / BC;
     int bh, j;
     decode_block(blockIdx.x, key_blocks, p.batch * p.heads, bh, j);
@@ -229,7 +232,8 @@ __global__ void __launch_bounds__(kThreads, 2) bwd_dkdv_split_kernel(FusedParams
     char* const p_lds = smem + 2 * kStageBytes;
     char* const ds_lds = p_lds + kPBytes;
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, h = lane >> 5, l32 = lane & 31;
+    const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, l32 = lane & 31;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, uniform
     const int wk = w & 1, wx = w >> 1;
     const int key_blocks = (p.n + BC - 1) / BC;
     int bh, j;
@@ -382,9 +386,10 @@ __global__ void __launch_bounds__(kThreads, 2) bwd_dq_kernel(FusedParams p) {
     constexpr int BR = 128, BC = 64, KS = D / 16, MT = D / 32;
     constexpr int kTileBytes = BC * D * 2;
     constexpr int kStageBytes = 2 * kTileBytes;
-    extern __shared__ __attribute__((aligned(16))) char smem[];
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, h = lane >> 5, l32 = lane & 31;
+    const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, l32 = lane & 31;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, uniform
     const int q_blocks = (p.n + BR - 1) / BR;
     int bh, blk;
     decode_block(blockIdx.x, q_blocks, p.batch * p.heads, bh, blk);
@@ -428,6 +433,8 @@ __global__ void __launch_bounds__(kThreads, 2) bwd_dq_kernel(FusedParams p) {
         for (int i = 0; i < 16; ++i) dq[mt][i] = 0.f;
 
     const float c = p.scale * kLog2e;
+    FragOffsets<D> fo;
+    fo.init(lane);
     // K and V tiles go straight from global memory into the LDS stage that was last read one
     // iteration ago; rows past n repeat the last row and are masked below.
     auto fetch = [&](int j0, int stage) {
@@ -440,49 +447,65 @@ __global__ void __launch_bounds__(kThreads, 2) bwd_dq_kernel(FusedParams p) {
     wait_direct_loads();
     __syncthreads();
 
-    for (int it = 0; it < n_it; ++it) {
+    // One streamed tile.  `masked` selects the copy of the body that applies the causal / tail
+    // bound; the other copy has no mask arithmetic at all.
+    auto tile = [&](int it, int j0, auto masked) {
+        const int k_off = (it & 1) * kStageBytes;  // K tile; the V tile follows it
+        // the two 32-key halves one after the other: half the score registers live at a time
+#pragma unroll
+        for (int T = 0; T < 2; ++T) {
+            f32x16 st, dpt;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) { st[i] = 0.f; dpt[i] = 0.f; }
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) st = mfma32(fo.frag(smem, k_off, 32 * T, ks), qf[ks], st);
+            __builtin_amdgcn_sched_barrier(0);  // keep the V fragments from being fetched this early
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) dpt = mfma32(fo.frag(smem, k_off + kTileBytes, 32 * T, ks), gf[ks], dpt);
+            __builtin_amdgcn_sched_barrier(0);
+            // key j0 + 32T + 8g + 4h + r is visible iff 8g + r <= lim (one per-lane bound)
+            const int lim = (p.causal ? min(q, p.n - 1) : p.n - 1) - j0 - 32 * T - 4 * h;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                float pv = __builtin_amdgcn_exp2f(st[i] * c - lse2);
+                if constexpr (decltype(masked)::value) pv = (8 * (i >> 2) + (i & 3) > lim) ? 0.f : pv;
+                dpt[i] = pv * (dpt[i] - dl);
+            }
+            bf16x8 dsb[2];
+#pragma unroll
+            for (int ss = 0; ss < 2; ++ss) dsb[ss] = acc_to_operand(dpt, ss);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int ss = 0; ss < 2; ++ss)
+                    dq[mt] = mfma32(fo.frag_t(smem, k_off, mt, 32 * T + 16 * ss), dsb[ss], dq[mt]);
+            __builtin_amdgcn_sched_barrier(0);  // the next half starts after this one is issued
+        }
+    };
+    // Tiles come in ascending key order, so those that need the bound (they straddle the
+    // diagonal or the end of the sequence) are the last ones: a mask-free loop first, then a
+    // masked loop.  Waves may switch loops at different tiles; both loops run the same barriers.
+    auto needs_mask = [&](int j0) { return (p.causal && (j0 + BC - 1 > i0 + 32 * w)) || (j0 + BC > p.n); };
+    int it = 0;
+    for (; it < n_it; ++it) {
         const int j0 = j0_next;
-        const bool more = it + 1 < n_it;
-        if (more) {
+        if (needs_mask(j0)) break;
+        if (it + 1 < n_it) {
             j0_next = tile_start(it + 1);
             fetch(j0_next, (it + 1) & 1);
         }
-        const char* ks_t = smem + (it & 1) * kStageBytes;
-        const char* vs_t = ks_t + kTileBytes;
-
-        // causal: this wave's last query precedes the tile's first key -> nothing visible
-        const bool skip = p.causal && (i0 + 32 * w + 31 < j0);
-        if (!skip) {
-            const bool need_mask = (p.causal && (j0 + BC - 1 > i0 + 32 * w)) || (j0 + BC > p.n);
-            // the two 32-key halves one after the other: half the score registers live at a time
-#pragma unroll
-            for (int T = 0; T < 2; ++T) {
-                f32x16 st, dpt;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) { st[i] = 0.f; dpt[i] = 0.f; }
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) st = mfma32(load_frag<D>(ks_t, 32 * T, ks, lane), qf[ks], st);
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) dpt = mfma32(load_frag<D>(vs_t, 32 * T, ks, lane), gf[ks], dpt);
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    float pv = __builtin_amdgcn_exp2f(st[i] * c - lse2);
-                    if (need_mask) {
-                        const int key = j0 + 32 * T + acc_row(i, h);
-                        if (key >= p.n || (p.causal && key > q)) pv = 0.f;
-                    }
-                    dpt[i] = pv * (dpt[i] - dl);
-                }
-                bf16x8 dsb[2];
-#pragma unroll
-                for (int ss = 0; ss < 2; ++ss) dsb[ss] = acc_to_operand(dpt, ss);
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                    for (int ss = 0; ss < 2; ++ss)
-                        dq[mt] = mfma32(load_frag_t<D>(ks_t, 32 * mt, 32 * T + 16 * ss, lane), dsb[ss], dq[mt]);
-            }
+        tile(it, j0, std::false_type{});
+        wait_direct_loads();
+        __syncthreads();
+    }
+    for (; it < n_it; ++it) {
+        const int j0 = j0_next;
+        if (it + 1 < n_it) {
+            j0_next = tile_start(it + 1);
+            fetch(j0_next, (it + 1) & 1);
         }
+        // causal: this wave's last query precedes the tile's first key -> nothing visible
+        if (!(p.causal && (i0 + 32 * w + 31 < j0))) tile(it, j0, std::true_type{});
         wait_direct_loads();
         __syncthreads();
     }

@@ -100,6 +100,38 @@ __device__ __forceinline__ bf16x8 load_frag_t(const char* tile, int col0, int ro
     return __builtin_bit_cast(bf16x8, r);
 }
 
+// The same two fetches with the lane-dependent part of the address hoisted out of the hot
+// loop.  The swizzle is an XOR on the chunk field (bits 4..7 of the byte offset), tiles start on
+// 256-byte boundaries and rows that are a multiple of 16 apart share their swizzle term, so
+//   offset(ks)  = (tile + rm0) ^ (ks << 5)            + row0 * row_bytes      (load_frag)
+//   offset(mt)  = (tile + tr0) ^ (mt << 6) [^ 32 for the rows + 8 half] + ...  (load_frag_t)
+// i.e. one per-lane base per tile, one XOR per fetch and a compile-time immediate.
+template <int D>
+struct FragOffsets {
+    int rm0, tr0;
+    __device__ __forceinline__ void init(int lane) {
+        rm0 = tile_off<D>(lane & 31, lane >> 5);
+        const int s = lane & 15;
+        const int col = 16 * ((lane >> 4) & 1) + 4 * (s & 3);
+        tr0 = tile_off<D>(4 * (lane >> 5) + (s >> 2), col >> 3) + ((col & 4) << 1);
+    }
+    // tile_off: byte offset of the tile inside `lds` (multiple of 256); rows row0 + l % 32 with
+    // row0 a multiple of 16
+    __device__ __forceinline__ bf16x8 frag(const char* lds, int tile_off_bytes, int row0, int ks) const {
+        const int a = (tile_off_bytes + rm0) ^ (ks << 5);
+        return *reinterpret_cast<const bf16x8*>(lds + a + row0 * (D * 2));
+    }
+    // columns 32 mt + l % 32; rows row16 + 8 (t / 4) + 4h + t % 4 with row16 a multiple of 16
+    __device__ __forceinline__ bf16x8 frag_t(const char* lds, int tile_off_bytes, int mt, int row16) const {
+        const int a = (tile_off_bytes + tr0) ^ (mt << 6);
+        i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 ATTN_LDS*)(lds + a + row16 * (D * 2)));
+        i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 ATTN_LDS*)(lds + (a ^ 32) + (row16 + 8) * (D * 2)));
+        typedef short i16x8 __attribute__((ext_vector_type(8)));
+        i16x8 r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(bf16x8, r);
+    }
+};
+
 // Operand whose k index runs along the tile's contiguous dimension, but with the k order of
 // load_frag_t (element t of half h <-> column 16 ks + 8 (t / 4) + 4h + t % 4), for products
 // whose other operand is read transposed.
@@ -154,7 +186,7 @@ __device__ __forceinline__ void load_tile_direct(const __bf16* base, long ld, in
     constexpr int kRowsPerInst = 1024 / (D * 2);
     constexpr int kInst = ROWS / (4 * kRowsPerInst);
     static_assert(ROWS % (4 * kRowsPerInst) == 0, "tile must split evenly over four waves");
-    const int lane = tid & 63, w = tid >> 6;
+    const int lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
 #pragma unroll
     for (int u = 0; u < kInst; ++u) {
         const int row = (u * 4 + w) * kRowsPerInst + lane / (D / 8);

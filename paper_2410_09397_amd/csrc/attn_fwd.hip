@@ -20,7 +20,8 @@ __global__ void __launch_bounds__(kThreads, 2) fwd_kernel(FusedParams p) {
     constexpr int kStageBytes = 2 * kTileBytes;
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, h = lane >> 5, l32 = lane & 31;
+    const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, l32 = lane & 31;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, uniform
     const int q_blocks = (p.n + BR - 1) / BR;
     int bh, blk;
     decode_block(blockIdx.x, q_blocks, p.batch * p.heads, bh, blk);

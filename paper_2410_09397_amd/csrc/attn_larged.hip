@@ -70,7 +70,8 @@ __global__ void __launch_bounds__(kThreads, 2) ld_scores_kernel(LargeDParams p) 
     constexpr int kTile = 128 * BK * 2;                       // bytes per operand tile
     constexpr int kOps = MODE == kBackward ? 4 : 2;           // K, Q (+ V, dO)
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, h = lane >> 5, l32 = lane & 31;
+    const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, l32 = lane & 31;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, uniform
     const int wm = w >> 1, wn = w & 1;
     const int nb = p.npad / 128;
     const int bh = blockIdx.z;
@@ -244,7 +245,8 @@ __global__ void __launch_bounds__(kThreads, 2) ld_gemm_kernel(LargeDParams p, Ge
     constexpr int BK = 64;
     constexpr int kTile = 128 * BK * 2;
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, h = lane >> 5, l32 = lane & 31;
+    const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, l32 = lane & 31;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, uniform
     const int wm = w >> 1, wn = w & 1;
     const int bh = blockIdx.z, mb = blockIdx.y, n0 = blockIdx.x * 128, m0 = mb * 128;
     const long base = (long)(bh / p.heads) * p.stride_b + (long)(bh % p.heads) * p.stride_h;
