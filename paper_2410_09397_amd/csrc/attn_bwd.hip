@@ -228,9 +228,7 @@ __global__ void __launch_bounds__(kThreads, 2) bwd_dkdv_split_kernel(FusedParams
     constexpr int kTileBytes = BR * D * 2;
     constexpr int kStageBytes = 2 * kTileBytes;
     constexpr int kPBytes = BC * BR * 2;
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    char* const p_lds = smem + 2 * kStageBytes;
-    char* const ds_lds = p_lds + kPBytes;
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, l32 = lane & 31;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, uniform
@@ -293,29 +291,39 @@ __global__ void __launch_bounds__(kThreads, 2) bwd_dkdv_split_kernel(FusedParams
     wait_direct_loads();
     __syncthreads();
 
-    for (int it = 0; it < n_it; ++it) {
-        const int i0 = i0_next;
-        const bool more = it + 1 < n_it;
-        if (more) i0_next = tile_start(it + 1);
+    FragOffsets<D> fo;    // Q / dO tiles
+    FragOffsets<BC> fp;   // P / dS tiles
+    fo.init(lane);
+    fp.init(lane);
+    constexpr int kPOff = 2 * kStageBytes, kDsOff = kPOff + kPBytes;
+    // this lane's 8-byte slot of group g in the [query][key] tiles: p_wr ^ (g << 4)
+    const int p_wr = tile_off<BC>(32 * wx + l32, 4 * wk) + 8 * h;
+
+    // One streamed query tile (two barriers).  `masked` selects the copy of phase 1 that applies
+    // the causal bound.
+    auto tile = [&](int it, int i0, bool skip, auto masked) {
         const float lse_cur = row_ok ? lse_raw * kLog2e : __builtin_inff();
         const float delta_cur = row_ok ? delta_raw : 0.f;
-        if (more) fetch(i0_next, (it + 1) & 1);  // that stage was last read before barrier B
-        const char* qs = smem + (it & 1) * kStageBytes;
-        const char* dos = qs + kTileBytes;
-        const bool skip = p.causal && (i0 + BR - 1 < j0);  // uniform over the workgroup
-
+        if (it + 1 < n_it) {
+            i0_next = tile_start(it + 1);
+            fetch(i0_next, (it + 1) & 1);  // that stage was last read before barrier B
+        }
+        const int q_off = (it & 1) * kStageBytes;  // Q tile; the dO tile follows it
         if (!skip) {
             // ---- phase 1: S^T, dP^T for (key half wk) x (query half wx); the resident K / V
             // fragments serve as A operands, so a lane holds one query and lse2 / delta are scalars
             f32x16 s, dp;
 #pragma unroll
             for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
+            const int qrow_off = q_off + 32 * wx * (D * 2);
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) s = mfma32(kf[ks], load_frag<D>(qs, 32 * wx, ks, lane), s);
+            for (int ks = 0; ks < KS; ++ks) s = mfma32(kf[ks], fo.frag(smem, qrow_off, 0, ks), s);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) dp = mfma32(vf[ks], load_frag<D>(dos, 32 * wx, ks, lane), dp);
-            const bool need_mask = p.causal && (i0 < j0 + BC - 1);
-            const int q = i0 + 32 * wx + l32;
+            for (int ks = 0; ks < KS; ++ks) dp = mfma32(vf[ks], fo.frag(smem, qrow_off + kTileBytes, 0, ks), dp);
+            __builtin_amdgcn_sched_barrier(0);
+            // key j0 + 32 wk + 8g + 4h + r is visible to this lane's query iff 8g + r <= lim
+            const int lim = i0 + 32 * wx + l32 - j0 - 32 * wk - 4 * h;
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 float pv[4], dsv[4];
@@ -323,19 +331,19 @@ __global__ void __launch_bounds__(kThreads, 2) bwd_dkdv_split_kernel(FusedParams
                 for (int r = 0; r < 4; ++r) {
                     const int i = 4 * g + r;
                     float v = __builtin_amdgcn_exp2f(s[i] * c - lse_cur);
-                    if (need_mask && j0 + 32 * wk + 8 * g + 4 * h + r > q) v = 0.f;
+                    if constexpr (decltype(masked)::value) v = (8 * g + r > lim) ? 0.f : v;
                     pv[r] = v;
                     dsv[r] = v * (dp[i] - delta_cur);
                 }
                 // [query][key] tiles: four consecutive keys of this lane's query
-                const int off = tile_off<BC>(32 * wx + l32, 4 * wk + g) + 8 * h;
+                const int off = p_wr ^ (g << 4);
                 u32x2 a, b;
                 a[0] = pack_bf16(pv[0], pv[1]);
                 a[1] = pack_bf16(pv[2], pv[3]);
                 b[0] = pack_bf16(dsv[0], dsv[1]);
                 b[1] = pack_bf16(dsv[2], dsv[3]);
-                *reinterpret_cast<u32x2*>(p_lds + off) = a;
-                *reinterpret_cast<u32x2*>(ds_lds + off) = b;
+                *reinterpret_cast<u32x2*>(smem + kPOff + off) = a;
+                *reinterpret_cast<u32x2*>(smem + kDsOff + off) = b;
             }
         }
         lds_barrier();  // P, dS visible; the tile copies for the next iteration stay in flight
@@ -343,18 +351,27 @@ __global__ void __launch_bounds__(kThreads, 2) bwd_dkdv_split_kernel(FusedParams
             // ---- phase 2: d-half wx of dV^T, dK^T for key half wk over the 64 queries
 #pragma unroll
             for (int ks = 0; ks < BR / 16; ++ks) {
-                const bf16x8 bp = load_frag_t<BC>(p_lds, 32 * wk, 16 * ks, lane);
-                const bf16x8 bs = load_frag_t<BC>(ds_lds, 32 * wk, 16 * ks, lane);
+                const bf16x8 bp = fp.frag_t(smem, kPOff, wk, 16 * ks);
+                const bf16x8 bs = fp.frag_t(smem, kDsOff, wk, 16 * ks);
 #pragma unroll
                 for (int m = 0; m < MH; ++m) {
-                    dv[m] = mfma32(load_frag_t<D>(dos, 32 * (MH * wx + m), 16 * ks, lane), bp, dv[m]);
-                    dk[m] = mfma32(load_frag_t<D>(qs, 32 * (MH * wx + m), 16 * ks, lane), bs, dk[m]);
+                    dv[m] = mfma32(fo.frag_t(smem, q_off + kTileBytes, MH * wx + m, 16 * ks), bp, dv[m]);
+                    dk[m] = mfma32(fo.frag_t(smem, q_off, MH * wx + m, 16 * ks), bs, dk[m]);
                 }
             }
         }
         wait_direct_loads();
         __syncthreads();
+    };
+    // Query tiles come in ascending order: under the causal rule the ones that straddle the
+    // diagonal (or lie wholly above it) are the first, then everything is visible.
+    int it = 0;
+    for (; it < n_it; ++it) {
+        const int i0 = i0_next;
+        if (!(p.causal && i0 < j0 + BC - 1)) break;
+        tile(it, i0, i0 + BR - 1 < j0, std::true_type{});
     }
+    for (; it < n_it; ++it) tile(it, i0_next, false, std::false_type{});
 
     if (key < p.n) {
         __bf16* dk_row = p.dK + base + (long)key * ld;

@@ -2,6 +2,8 @@
 // definition, Sec. 3.1; A, l, f, O of App. B.4), evaluated per block of 128 queries with a
 // running maximum so that no n x n matrix is formed.  The paper gives no forward algorithm;
 // the streaming-softmax tiling is prior art, the kernel is written for gfx950.
+#include <type_traits>
+
 #include "attn_common.hpp"
 #include "attn_internal.hpp"
 
@@ -18,7 +20,7 @@ __global__ void __launch_bounds__(kThreads, 2) fwd_kernel(FusedParams p) {
     constexpr int BR = 128, BC = 64, KS = D / 16, MT = D / 32;
     constexpr int kTileBytes = BC * D * 2;
     constexpr int kStageBytes = 2 * kTileBytes;
-    extern __shared__ __attribute__((aligned(16))) char smem[];
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, l32 = lane & 31;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, uniform
@@ -57,10 +59,24 @@ __global__ void __launch_bounds__(kThreads, 2) fwd_kernel(FusedParams p) {
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int i = 0; i < 16; ++i) o[mt][i] = 0.f;
-    float m_run = -__builtin_inff();  // running maximum of c * s (log2 domain)
-    float l_run = 0.f;                // this lane's share of sum exp2(c s - m_run)
+    float m_run = -__builtin_inff();  // running maximum of scale * log2(e) * s
+    float l_run = 0.f;                // this lane's share of sum exp2(scaled s - m_run)
 
-    const float c = p.scale * kLog2e;
+    // Scores are kept raw in the accumulators and scaled inside the exponential: with
+    // cs = |scale| log2(e) > 0 the row maximum commutes with the scaling.  A negative scale is
+    // moved into Q (sign flip of the resident fragments), a zero scale becomes a denormal-sized
+    // positive one so that masked (-inf) scores stay -inf.
+    const float cs = fmaxf(fabsf(p.scale) * kLog2e, 1.17549435e-38f);
+    if (p.scale < 0.f) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            u32x4 v = __builtin_bit_cast(u32x4, qf[ks]);
+            v ^= 0x80008000u;
+            qf[ks] = __builtin_bit_cast(bf16x8, v);
+        }
+    }
+    FragOffsets<D> fo;
+    fo.init(lane);
     // K and V tiles go straight from global memory into the LDS stage that was last read one
     // iteration ago; rows past n repeat the last row and are masked below.
     auto fetch = [&](int j0, int stage) {
@@ -73,74 +89,90 @@ __global__ void __launch_bounds__(kThreads, 2) fwd_kernel(FusedParams p) {
     wait_direct_loads();
     __syncthreads();
 
-    for (int it = 0; it < n_it; ++it) {
-        const int j0 = j0_next;
-        const bool more = it + 1 < n_it;
-        if (more) {
-            j0_next = tile_start(it + 1);
-            fetch(j0_next, (it + 1) & 1);
+    // One streamed tile; `masked` selects the copy of the body that applies the causal / tail bound.
+    auto tile = [&](int it, int j0, auto masked) {
+        const int k_off = (it & 1) * kStageBytes;  // K tile; the V tile follows it
+        f32x16 st[2];
+#pragma unroll
+        for (int T = 0; T < 2; ++T)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) st[T][i] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int T = 0; T < 2; ++T) st[T] = mfma32(fo.frag(smem, k_off, 32 * T, ks), qf[ks], st[T]);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (decltype(masked)::value) {
+            // key j0 + 32T + 8g + 4h + r is visible iff 32T + 8g + r <= lim (one per-lane bound)
+            const int lim = (p.causal ? min(q, p.n - 1) : p.n - 1) - j0 - 4 * h;
+#pragma unroll
+            for (int T = 0; T < 2; ++T)
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    st[T][i] = (32 * T + 8 * (i >> 2) + (i & 3) > lim) ? -__builtin_inff() : st[T][i];
         }
-        const char* ks_t = smem + (it & 1) * kStageBytes;
-        const char* vs_t = ks_t + kTileBytes;
-
-        const bool skip = p.causal && (i0 + 32 * w + 31 < j0);
-        if (!skip) {
-            f32x16 st[2];
+        float mx = fmaxf(st[0][0], st[1][0]);
 #pragma unroll
-            for (int T = 0; T < 2; ++T)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) st[T][i] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-                for (int T = 0; T < 2; ++T) st[T] = mfma32(load_frag<D>(ks_t, 32 * T, ks, lane), qf[ks], st[T]);
-
-            const bool need_mask = (p.causal && (j0 + BC - 1 > i0 + 32 * w)) || (j0 + BC > p.n);
-            float mx = -__builtin_inff();
-#pragma unroll
-            for (int T = 0; T < 2; ++T)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    float x = st[T][i] * c;
-                    if (need_mask) {
-                        const int key = j0 + 32 * T + acc_row(i, h);
-                        if (key >= p.n || (p.causal && key > q)) x = -__builtin_inff();
-                    }
-                    st[T][i] = x;
-                    mx = fmaxf(mx, x);
-                }
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m_run, mx);
-            const float m_use = (m_new == -__builtin_inff()) ? 0.f : m_new;  // nothing visible yet
+        for (int i = 1; i < 16; ++i) mx = fmaxf(mx, fmaxf(st[0][i], st[1][i]));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run, mx * cs);
+        const float m_use = (m_new == -__builtin_inff()) ? 0.f : m_new;  // nothing visible yet
+        if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {  // some row's maximum moved: rescale
             const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-            m_run = m_new;
-            float sum = 0.f;
-#pragma unroll
-            for (int T = 0; T < 2; ++T)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const float pv = __builtin_amdgcn_exp2f(st[T][i] - m_use);
-                    st[T][i] = pv;
-                    sum += pv;
-                }
-            l_run = l_run * alpha + sum;
+            l_run *= alpha;
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) o[mt][i] *= alpha;
-            bf16x8 pb[2][2];
+        }
+        m_run = m_new;
+        float sum = 0.f;
+#pragma unroll
+        for (int T = 0; T < 2; ++T)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float pv = __builtin_amdgcn_exp2f(fmaf(st[T][i], cs, -m_use));
+                st[T][i] = pv;
+                sum += pv;
+            }
+        l_run += sum;
+        bf16x8 pb[2][2];
+#pragma unroll
+        for (int T = 0; T < 2; ++T)
+#pragma unroll
+            for (int ss = 0; ss < 2; ++ss) pb[T][ss] = acc_to_operand(st[T], ss);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int T = 0; T < 2; ++T)
 #pragma unroll
-                for (int ss = 0; ss < 2; ++ss) pb[T][ss] = acc_to_operand(st[T], ss);
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                for (int T = 0; T < 2; ++T)
-#pragma unroll
-                    for (int ss = 0; ss < 2; ++ss)
-                        o[mt] = mfma32(load_frag_t<D>(vs_t, 32 * mt, 32 * T + 16 * ss, lane), pb[T][ss], o[mt]);
+                for (int ss = 0; ss < 2; ++ss)
+                    o[mt] = mfma32(fo.frag_t(smem, k_off + kTileBytes, mt, 32 * T + 16 * ss), pb[T][ss], o[mt]);
+    };
+    // Tiles come in ascending key order, so those that need the bound (they straddle the
+    // diagonal or the end of the sequence) are the last ones: a mask-free loop first, then a
+    // masked loop.  Waves may switch loops at different tiles; both loops run the same barriers.
+    auto needs_mask = [&](int j0) { return (p.causal && (j0 + BC - 1 > i0 + 32 * w)) || (j0 + BC > p.n); };
+    int it = 0;
+    for (; it < n_it; ++it) {
+        const int j0 = j0_next;
+        if (needs_mask(j0)) break;
+        if (it + 1 < n_it) {
+            j0_next = tile_start(it + 1);
+            fetch(j0_next, (it + 1) & 1);
         }
+        tile(it, j0, std::false_type{});
+        wait_direct_loads();
+        __syncthreads();
+    }
+    for (; it < n_it; ++it) {
+        const int j0 = j0_next;
+        if (it + 1 < n_it) {
+            j0_next = tile_start(it + 1);
+            fetch(j0_next, (it + 1) & 1);
+        }
+        // causal: this wave's last query precedes the tile's first key -> nothing visible
+        if (!(p.causal && (i0 + 32 * w + 31 < j0))) tile(it, j0, std::true_type{});
         wait_direct_loads();
         __syncthreads();
     }
