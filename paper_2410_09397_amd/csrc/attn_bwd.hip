@@ -317,10 +317,10 @@ __global__ void __launch_bounds__(kThreads, 2) bwd_dkdv_split_kernel(FusedParams
             for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
             const int qrow_off = q_off + 32 * wx * (D * 2);
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) s = mfma32(kf[ks], fo.frag(smem, qrow_off, 0, ks), s);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) dp = mfma32(vf[ks], fo.frag(smem, qrow_off + kTileBytes, 0, ks), dp);
+            for (int ks = 0; ks < KS; ++ks) {  // two independent accumulation chains, interleaved
+                s = mfma32(kf[ks], fo.frag(smem, qrow_off, 0, ks), s);
+                dp = mfma32(vf[ks], fo.frag(smem, qrow_off + kTileBytes, 0, ks), dp);
+            }
             __builtin_amdgcn_sched_barrier(0);
             // key j0 + 32 wk + 8g + 4h + r is visible to this lane's query iff 8g + r <= lim
             const int lim = i0 + 32 * wx + l32 - j0 - 32 * wk - 4 * h;
@@ -475,10 +475,10 @@ __global__ void __launch_bounds__(kThreads, 2) bwd_dq_kernel(FusedParams p) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) { st[i] = 0.f; dpt[i] = 0.f; }
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) st = mfma32(fo.frag(smem, k_off, 32 * T, ks), qf[ks], st);
-            __builtin_amdgcn_sched_barrier(0);  // keep the V fragments from being fetched this early
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) dpt = mfma32(fo.frag(smem, k_off + kTileBytes, 32 * T, ks), gf[ks], dpt);
+            for (int ks = 0; ks < KS; ++ks) {  // two independent accumulation chains, interleaved
+                st = mfma32(fo.frag(smem, k_off, 32 * T, ks), qf[ks], st);
+                dpt = mfma32(fo.frag(smem, k_off + kTileBytes, 32 * T, ks), gf[ks], dpt);
+            }
             __builtin_amdgcn_sched_barrier(0);
             // key j0 + 32T + 8g + 4h + r is visible iff 8g + r <= lim (one per-lane bound)
             const int lim = (p.causal ? min(q, p.n - 1) : p.n - 1) - j0 - 32 * T - 4 * h;
@@ -492,9 +492,9 @@ __global__ void __launch_bounds__(kThreads, 2) bwd_dq_kernel(FusedParams p) {
 #pragma unroll
             for (int ss = 0; ss < 2; ++ss) dsb[ss] = acc_to_operand(dpt, ss);
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
+            for (int ss = 0; ss < 2; ++ss)
 #pragma unroll
-                for (int ss = 0; ss < 2; ++ss)
+                for (int mt = 0; mt < MT; ++mt)  // innermost: consecutive MFMAs hit different accumulators
                     dq[mt] = mfma32(fo.frag_t(smem, k_off, mt, 32 * T + 16 * ss), dsb[ss], dq[mt]);
             __builtin_amdgcn_sched_barrier(0);  // the next half starts after this one is issued
         }

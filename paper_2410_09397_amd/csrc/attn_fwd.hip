@@ -142,11 +142,11 @@ __global__ void __launch_bounds__(kThreads, 2) fwd_kernel(FusedParams p) {
 #pragma unroll
             for (int ss = 0; ss < 2; ++ss) pb[T][ss] = acc_to_operand(st[T], ss);
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+        for (int T = 0; T < 2; ++T)
 #pragma unroll
-            for (int T = 0; T < 2; ++T)
+            for (int ss = 0; ss < 2; ++ss)
 #pragma unroll
-                for (int ss = 0; ss < 2; ++ss)
+                for (int mt = 0; mt < MT; ++mt)  // innermost: consecutive MFMAs hit different accumulators
                     o[mt] = mfma32(fo.frag_t(smem, k_off + kTileBytes, mt, 32 * T + 16 * ss), pb[T][ss], o[mt]);
     };
     // Tiles come in ascending key order, so those that need the bound (they straddle the

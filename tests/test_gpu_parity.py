@@ -118,6 +118,28 @@ def test_mask_logic_is_bit_exact(d, dtype, block):
         assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("scale", [-0.11, 0.0, 0.35])
+@pytest.mark.parametrize("d,dtype", [(128, "bf16"), (64, "bf16"), (512, "bf16"), (48, "f32")])
+def test_unusual_scales(scale, d, dtype):
+    """scale is any finite float: negative (the forward moves its sign into Q) and zero (uniform
+    attention over the visible keys) must match the oracle like the usual 1/sqrt(d)."""
+    from oracle import attn_oracle as orc
+    from paper_2410_09397_amd import attn
+    w = W("scale", 70, 1, 2, 200, d, dtype, causal=True)
+    inp = synth.make_inputs(w)
+    Q, K, V, dO = (to_dev(inp[t], w.dtype) for t in ("Q", "K", "V", "dO"))
+    O, LSE = attn.attn_fwd(Q, K, V, scale, causal=True)
+    dQ, dK, dV = attn.attn_bwd(Q, K, V, O, dO, LSE, scale, causal=True)
+    rO, rL = orc.attn_fwd(inp["Q"], inp["K"], inp["V"], scale, causal=True)
+    rg = orc.attn_bwd(inp["Q"], inp["K"], inp["V"], rO, inp["dO"], rL, scale, causal=True)
+    tol = TOL[dtype]
+    assert rel_err(to_np(O), rO) <= tol
+    assert np.abs(to_np(LSE) - rL).max() <= LSE_TOL[dtype] * max(1.0, np.abs(rL).max())
+    for name, g, r in zip(("dQ", "dK", "dV"), (dQ, dK, dV), rg):
+        den = max(np.abs(r).max(), 1e-30)
+        assert np.abs(to_np(g) - r).max() <= tol * den + (1e-6 if scale == 0.0 else 0.0), name
+
+
 def test_backward_is_deterministic():
     """No atomics anywhere: two runs give bit-identical dQ, dK, dV."""
     import torch
