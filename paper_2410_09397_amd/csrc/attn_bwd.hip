@@ -224,7 +224,7 @@ __global__ void __launch_bounds__(kThreads, D == 64 ? 2 : 1) bwd_dkdv_kernel(Fus
 //            transposing LDS loads.
 template <int D>
 __global__ void __launch_bounds__(kThreads, 2) bwd_dkdv_split_kernel(FusedParams p) {
-    constexpr int BR = 64, BC = 64, KS = D / 16, MH = D / 64;  // MH m-tiles per d-half
+    constexpr int BR = 64, BC = 64, KS = D / 16, MT = D / 32;
     constexpr int kTileBytes = BR * D * 2;
     constexpr int kStageBytes = 2 * kTileBytes;
     constexpr int kPBytes = BC * BR * 2;
@@ -266,11 +266,13 @@ __global__ void __launch_bounds__(kThreads, 2) bwd_dkdv_split_kernel(FusedParams
             }
         }
     }
-    f32x16 dk[MH], dv[MH];
+    // phase-2 role of this wave: wx = 0 accumulates dV^T (from P and dO^T), wx = 1 dK^T (from dS
+    // and Q^T), each for all of d and key half wk
+    f32x16 acc[MT];
 #pragma unroll
-    for (int m = 0; m < MH; ++m)
+    for (int m = 0; m < MT; ++m)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) { dk[m][i] = 0.f; dv[m][i] = 0.f; }
+        for (int i = 0; i < 16; ++i) acc[m][i] = 0.f;
 
     const float c = p.scale * kLog2e;
     // Row i0 + 32 wx + l32 of the tile being fetched.  The loaded values are not touched until
@@ -348,16 +350,15 @@ __global__ void __launch_bounds__(kThreads, 2) bwd_dkdv_split_kernel(FusedParams
         }
         lds_barrier();  // P, dS visible; the tile copies for the next iteration stay in flight
         if (!skip) {
-            // ---- phase 2: d-half wx of dV^T, dK^T for key half wk over the 64 queries
+            // ---- phase 2: dV^T = dO^T P (wx = 0) or dK^T = Q^T dS (wx = 1) for key half wk over
+            // the 64 queries: one B fragment feeds the MFMAs of all d
+            const int a_off = wx == 0 ? q_off + kTileBytes : q_off;
+            const int b_off = wx == 0 ? kPOff : kDsOff;
 #pragma unroll
             for (int ks = 0; ks < BR / 16; ++ks) {
-                const bf16x8 bp = fp.frag_t(smem, kPOff, wk, 16 * ks);
-                const bf16x8 bs = fp.frag_t(smem, kDsOff, wk, 16 * ks);
+                const bf16x8 b = fp.frag_t(smem, b_off, wk, 16 * ks);
 #pragma unroll
-                for (int m = 0; m < MH; ++m) {
-                    dv[m] = mfma32(fo.frag_t(smem, q_off + kTileBytes, MH * wx + m, 16 * ks), bp, dv[m]);
-                    dk[m] = mfma32(fo.frag_t(smem, q_off, MH * wx + m, 16 * ks), bs, dk[m]);
-                }
+                for (int m = 0; m < MT; ++m) acc[m] = mfma32(fo.frag_t(smem, a_off, m, 16 * ks), b, acc[m]);
             }
         }
         wait_direct_loads();
@@ -374,20 +375,16 @@ __global__ void __launch_bounds__(kThreads, 2) bwd_dkdv_split_kernel(FusedParams
     for (; it < n_it; ++it) tile(it, i0_next, false, std::false_type{});
 
     if (key < p.n) {
-        __bf16* dk_row = p.dK + base + (long)key * ld;
-        __bf16* dv_row = p.dV + base + (long)key * ld;
+        __bf16* row = (wx == 0 ? p.dV : p.dK) + base + (long)key * ld;
+        const float f = wx == 0 ? 1.f : p.scale;
 #pragma unroll
-        for (int m = 0; m < MH; ++m)
+        for (int m = 0; m < MT; ++m)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const int col = 32 * (MH * wx + m) + 8 * g + 4 * h;
-                u32x2 a, b;
-                a[0] = pack_bf16(dk[m][4 * g + 0] * p.scale, dk[m][4 * g + 1] * p.scale);
-                a[1] = pack_bf16(dk[m][4 * g + 2] * p.scale, dk[m][4 * g + 3] * p.scale);
-                b[0] = pack_bf16(dv[m][4 * g + 0], dv[m][4 * g + 1]);
-                b[1] = pack_bf16(dv[m][4 * g + 2], dv[m][4 * g + 3]);
-                *reinterpret_cast<u32x2*>(dk_row + col) = a;
-                *reinterpret_cast<u32x2*>(dv_row + col) = b;
+                u32x2 a;
+                a[0] = pack_bf16(acc[m][4 * g + 0] * f, acc[m][4 * g + 1] * f);
+                a[1] = pack_bf16(acc[m][4 * g + 2] * f, acc[m][4 * g + 3] * f);
+                *reinterpret_cast<u32x2*>(row + 32 * m + 8 * g + 4 * h) = a;
             }
     }
 }
