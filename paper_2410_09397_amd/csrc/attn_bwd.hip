@@ -293,6 +293,11 @@ __global__ void __launch_bounds__(kThreads, 2) bwd_dkdv_split_kernel(FusedParams
     wait_direct_loads();
     __syncthreads();
 
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        settle(kf[ks]);
+        settle(vf[ks]);
+    }
     FragOffsets<D> fo;    // Q / dO tiles
     FragOffsets<BC> fp;   // P / dS tiles
     fo.init(lane);
@@ -447,6 +452,13 @@ __global__ void __launch_bounds__(kThreads, 2) bwd_dq_kernel(FusedParams p) {
         for (int i = 0; i < 16; ++i) dq[mt][i] = 0.f;
 
     const float c = p.scale * kLog2e;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        settle(qf[ks]);
+        settle(gf[ks]);
+    }
+    settle(lse2);
+    settle(dl);
     FragOffsets<D> fo;
     fo.init(lane);
     // K and V tiles go straight from global memory into the LDS stage that was last read one

@@ -192,12 +192,26 @@ __device__ __forceinline__ void load_tile_direct(const __bf16* base, long ld, in
         const int row = (u * 4 + w) * kRowsPerInst + lane / (D / 8);
         const int c = (lane % (D / 8)) ^ swz<D>(row);
         const int grow = min(row_begin + row, rows_valid - 1);
-        __builtin_amdgcn_global_load_lds(
-            (const void __attribute__((address_space(1)))*)(base + (long)grow * ld + c * 8),
-            (void ATTN_LDS*)(tile + (u * 4 + w) * 1024), 16, 0, 0);
+        // Issued as inline assembly on purpose: for the builtin the compiler cannot tell which LDS
+        // bytes a copy in flight will write and drains all of them (s_waitcnt vmcnt(0)) before the
+        // next transposing LDS read, i.e. in the middle of the iteration.  Here the wait is ours:
+        // wait_direct_loads() right before the barrier that publishes the stage.
+        const unsigned dst = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(ATTN_LDS char*)(tile + (u * 4 + w) * 1024));
+        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+                     :
+                     : "s"(dst), "v"(base + (long)grow * ld + c * 8)
+                     : "memory");
     }
 }
 __device__ __forceinline__ void wait_direct_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// Marks a register value as used here.  Ordinary global loads issued before the streaming loop
+// must be complete before it starts: otherwise the compiler's own wait for them lands inside the
+// loop and, vmcnt being one in-order counter, also drains the tile copies in flight.
+template <typename T>
+__device__ __forceinline__ void settle(const T& v) {
+    asm volatile("" : : "v"(v));
+}
 
 // Workgroup barrier that orders LDS traffic only: it waits for this wave's LDS operations but
 // not for global loads still in flight (__syncthreads would also drain those).

@@ -75,6 +75,8 @@ __global__ void __launch_bounds__(kThreads, 2) fwd_kernel(FusedParams p) {
             qf[ks] = __builtin_bit_cast(bf16x8, v);
         }
     }
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) settle(qf[ks]);
     FragOffsets<D> fo;
     fo.init(lane);
     // K and V tiles go straight from global memory into the LDS stage that was last read one
