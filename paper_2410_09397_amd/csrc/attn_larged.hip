@@ -74,8 +74,25 @@ __global__ void __launch_bounds__(kThreads, 2) ld_scores_kernel(LargeDParams p) 
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, uniform
     const int wm = w >> 1, wn = w & 1;
     const int nb = p.npad / 128;
-    const int bh = blockIdx.z;
-    int kb = blockIdx.x, qb = blockIdx.y;
+    // 1-D grid; ids congruent mod 8 share an XCD and its 4 MB L2.  Each XCD gets a contiguous
+    // range of tiles, ordered so that 64 consecutive ones form an 8 x 8 block of (query, key)
+    // tiles: their 32 operand blocks (4 MB at d = 512) are what the L2 can keep.
+    int bh, kb, qb;
+    {
+        const int heads = p.batch * p.heads, total = nb * nb * heads;
+        int t = blockIdx.x;
+        if ((total & 7) == 0) t = (t >> 3) + (t & 7) * (total >> 3);
+        bh = t / (nb * nb);
+        const int tile = t % (nb * nb);
+        if ((nb & 7) == 0) {
+            const int region = tile >> 6, in = tile & 63, rpr = nb >> 3;  // regions per row
+            qb = (region / rpr) * 8 + (in >> 3);
+            kb = (region % rpr) * 8 + (in & 7);
+        } else {
+            qb = tile / nb;
+            kb = tile % nb;
+        }
+    }
     if (p.causal && kb > qb) return;  // whole tile above the diagonal: never read downstream
     const long base = (long)(bh / p.heads) * p.stride_b + (long)(bh % p.heads) * p.stride_h;
     const uint32_t ldb = (uint32_t)p.stride_n * 2;
@@ -248,7 +265,18 @@ __global__ void __launch_bounds__(kThreads, 2) ld_gemm_kernel(LargeDParams p, Ge
     const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, l32 = lane & 31;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, uniform
     const int wm = w >> 1, wn = w & 1;
-    const int bh = blockIdx.z, mb = blockIdx.y, n0 = blockIdx.x * 128, m0 = mb * 128;
+    // 1-D grid, XCD-contiguous like the scores kernel: the column tiles of one (head, row block)
+    // follow one another on one XCD and share its copy of the A operand
+    int bh, mb, n0;
+    {
+        const int nt = (p.d + 127) / 128, mbs = p.npad / 128, total = nt * mbs * p.batch * p.heads;
+        int t = blockIdx.x;
+        if ((total & 7) == 0) t = (t >> 3) + (t & 7) * (total >> 3);
+        n0 = (t % nt) * 128;
+        mb = (t / nt) % mbs;
+        bh = t / (nt * mbs);
+    }
+    const int m0 = mb * 128;
     const long base = (long)(bh / p.heads) * p.stride_b + (long)(bh % p.heads) * p.stride_h;
     const auto rA = make_rsrc(g.A + (long)bh * p.npad * p.npad, (uint32_t)((long)p.npad * p.npad * 2));
     const auto rB = make_rsrc(g.B + base, (uint32_t)(((long)(p.n - 1) * p.stride_n + p.d) * 2));
@@ -318,7 +346,7 @@ static hipError_t set_lds(const void* fn, int bytes) {
 template <bool A_KMAJOR>
 static void run_gemm(const LargeDParams& p, const __bf16* A, const __bf16* B, __bf16* C, float alpha,
                      hipStream_t stream) {
-    const dim3 grid((unsigned)((p.d + 127) / 128), (unsigned)(p.npad / 128), (unsigned)(p.batch * p.heads));
+    const dim3 grid((unsigned)(((p.d + 127) / 128) * (p.npad / 128) * p.batch * p.heads));
     GemmArgs g{A, B, C, alpha};
     hipLaunchKernelGGL(ld_gemm_kernel<A_KMAJOR>, grid, dim3(kThreads), 2 * 2 * 128 * 64 * 2, stream, p, g);
 }
@@ -335,7 +363,7 @@ hipError_t launch_larged(bool backward, const LargeDParams& p, hipStream_t strea
         configured = true;
     }
     const unsigned nb = (unsigned)(p.npad / 128), bh = (unsigned)(p.batch * p.heads);
-    const dim3 sgrid(nb, nb, bh), block(kThreads);
+    const dim3 sgrid(nb * nb * bh), block(kThreads);
     if (!backward) {
         hipLaunchKernelGGL(ld_scores_kernel<kStats>, sgrid, block, 2 * 2 * 128 * 32 * 2, stream, p);
         const long rows = (long)bh * p.n;
