@@ -143,13 +143,21 @@ __global__ void __launch_bounds__(kThreads, 2) fwd_kernel(FusedParams p) {
         for (int T = 0; T < 2; ++T)
 #pragma unroll
             for (int ss = 0; ss < 2; ++ss) pb[T][ss] = acc_to_operand(st[T], ss);
+        // O^T += V^T P^T in four groups of 16 keys; the V^T fragments of the next group are
+        // requested before the MFMAs of the current one so that LDS latency hides behind them
+        bf16x8 va[2][MT];
 #pragma unroll
-        for (int T = 0; T < 2; ++T)
+        for (int mt = 0; mt < MT; ++mt) va[0][mt] = fo.frag_t(smem, k_off + kTileBytes, mt, 0);
 #pragma unroll
-            for (int ss = 0; ss < 2; ++ss)
+        for (int g = 0; g < 4; ++g) {
+            if (g + 1 < 4) {
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt)  // innermost: consecutive MFMAs hit different accumulators
-                    o[mt] = mfma32(fo.frag_t(smem, k_off + kTileBytes, mt, 32 * T + 16 * ss), pb[T][ss], o[mt]);
+                for (int mt = 0; mt < MT; ++mt)
+                    va[(g + 1) & 1][mt] = fo.frag_t(smem, k_off + kTileBytes, mt, 16 * (g + 1));
+            }
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) o[mt] = mfma32(va[g & 1][mt], pb[g >> 1][g & 1], o[mt]);
+        }
     };
     // Tiles come in ascending key order, so those that need the bound (they straddle the
     // diagonal or the end of the sequence) are the last ones: a mask-free loop first, then a
