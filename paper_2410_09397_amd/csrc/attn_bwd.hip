@@ -359,11 +359,19 @@ __global__ void __launch_bounds__(kThreads, 2) bwd_dkdv_split_kernel(FusedParams
             // the 64 queries: one B fragment feeds the MFMAs of all d
             const int a_off = wx == 0 ? q_off + kTileBytes : q_off;
             const int b_off = wx == 0 ? kPOff : kDsOff;
+            bf16x8 at[2][MT], bt[2];
 #pragma unroll
-            for (int ks = 0; ks < BR / 16; ++ks) {
-                const bf16x8 b = fp.frag_t(smem, b_off, wk, 16 * ks);
+            for (int m = 0; m < MT; ++m) at[0][m] = fo.frag_t(smem, a_off, m, 0);
+            bt[0] = fp.frag_t(smem, b_off, wk, 0);
 #pragma unroll
-                for (int m = 0; m < MT; ++m) acc[m] = mfma32(fo.frag_t(smem, a_off, m, 16 * ks), b, acc[m]);
+            for (int ks = 0; ks < BR / 16; ++ks) {  // fragments of the next 16 queries requested ahead
+                if (ks + 1 < BR / 16) {
+#pragma unroll
+                    for (int m = 0; m < MT; ++m) at[(ks + 1) & 1][m] = fo.frag_t(smem, a_off, m, 16 * (ks + 1));
+                    bt[(ks + 1) & 1] = fp.frag_t(smem, b_off, wk, 16 * (ks + 1));
+                }
+#pragma unroll
+                for (int m = 0; m < MT; ++m) acc[m] = mfma32(at[ks & 1][m], bt[ks & 1], acc[m]);
             }
         }
         wait_direct_loads();
@@ -497,14 +505,20 @@ __global__ void __launch_bounds__(kThreads, 2) bwd_dq_kernel(FusedParams p) {
                 if constexpr (decltype(masked)::value) pv = (8 * (i >> 2) + (i & 3) > lim) ? 0.f : pv;
                 dpt[i] = pv * (dpt[i] - dl);
             }
-            bf16x8 dsb[2];
+            bf16x8 dsb[2], kt[2][MT];
 #pragma unroll
             for (int ss = 0; ss < 2; ++ss) dsb[ss] = acc_to_operand(dpt, ss);
 #pragma unroll
-            for (int ss = 0; ss < 2; ++ss)
+            for (int mt = 0; mt < MT; ++mt) kt[0][mt] = fo.frag_t(smem, k_off, mt, 32 * T);
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt)  // innermost: consecutive MFMAs hit different accumulators
-                    dq[mt] = mfma32(fo.frag_t(smem, k_off, mt, 32 * T + 16 * ss), dsb[ss], dq[mt]);
+            for (int ss = 0; ss < 2; ++ss) {  // K^T fragments of the next 16 keys requested ahead
+                if (ss == 0) {
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) kt[1][mt] = fo.frag_t(smem, k_off, mt, 32 * T + 16);
+                }
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) dq[mt] = mfma32(kt[ss][mt], dsb[ss], dq[mt]);
+            }
             __builtin_amdgcn_sched_barrier(0);  // the next half starts after this one is issued
         }
     };
