@@ -14,24 +14,25 @@
 namespace attn {
 
 // --------------------------------------------------------------------------------- delta
-// One wavefront per row; lanes read 16-byte chunks and the row sum is a shuffle reduction.
+// d / 8 consecutive lanes share one row (16-byte chunks, all 64 lanes busy for d <= 512); the row
+// sum is a shuffle reduction inside that lane group.  d / 8 must be a power of two <= 64.
 __global__ void __launch_bounds__(kThreads) delta_kernel(FusedParams p, int d) {
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int cpr = d >> 3;  // chunks (lanes) per row
     const long rows = (long)p.batch * p.heads * p.n;
-    const long r = (long)blockIdx.x * 4 + w;
-    if (r >= rows) return;
-    const int bh = (int)(r / p.n), i = (int)(r % p.n);
-    const long base = (long)(bh / p.heads) * p.stride_b + (long)(bh % p.heads) * p.stride_h + (long)i * p.stride_n;
+    const long f = (long)blockIdx.x * kThreads + threadIdx.x;
+    const long r = f / cpr;
+    const int c = (int)(f % cpr);
     float acc = 0.f;
-    for (int c = lane; c < d / 8; c += 64) {
-        bf16x8 o = *reinterpret_cast<const bf16x8*>(p.O + base + c * 8);
-        bf16x8 g = *reinterpret_cast<const bf16x8*>(p.dO + base + c * 8);
+    if (r < rows) {
+        const int bh = (int)(r / p.n), i = (int)(r % p.n);
+        const long off = (long)(bh / p.heads) * p.stride_b + (long)(bh % p.heads) * p.stride_h + (long)i * p.stride_n + c * 8;
+        const bf16x8 o = *reinterpret_cast<const bf16x8*>(p.O + off);
+        const bf16x8 g = *reinterpret_cast<const bf16x8*>(p.dO + off);
 #pragma unroll
         for (int t = 0; t < 8; ++t) acc += (float)o[t] * (float)g[t];
     }
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
-    if (lane == 0) p.delta[r] = acc;
+    for (int m = cpr >> 1; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
+    if (r < rows && c == 0) p.delta[r] = acc;
 }
 
 // ------------------------------------------------------------------------------- dK, dV
@@ -592,8 +593,8 @@ __global__ void __launch_bounds__(kThreads, QT == 1 ? 2 : 1) bwd_dq_kernel(Fused
 
 // ------------------------------------------------------------------------------ launchers
 void launch_delta(const FusedParams& p, int d, hipStream_t stream) {
-    const long rows = (long)p.batch * p.heads * p.n;
-    hipLaunchKernelGGL(delta_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(kThreads), 0, stream, p, d);
+    const long lanes = (long)p.batch * p.heads * p.n * (d / 8);
+    hipLaunchKernelGGL(delta_kernel, dim3((unsigned)((lanes + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream, p, d);
 }
 
 template <int D>
