@@ -36,200 +36,23 @@ __global__ void __launch_bounds__(kThreads) delta_kernel(FusedParams p, int d) {
 }
 
 // ------------------------------------------------------------------------------- dK, dV
-// Wave w owns keys j0 + 32w .. +31: their K and V rows stay in registers as B operands.
-// Per query tile (64 rows, two 32-row halves T):
-//   S[T]  = Q_T K_w^T, dP[T] = dO_T V_w^T           accumulator: lane <-> key, register <-> query
-//   P = exp2(c S - lse2), dS = P (dP - delta)        in registers, then packed to bf16
-//   dV_w^T += dO_T^T P,   dK_w^T += Q_T^T dS         accumulators are B operands as they stand;
-//                                                    Q^T / dO^T come from transposed LDS reads
-template <int D>
-__global__ void __launch_bounds__(kThreads, D == 64 ? 2 : 1) bwd_dkdv_kernel(FusedParams p) {
-    constexpr int BR = 64, BC = 128, KS = D / 16, MT = D / 32;
-    constexpr int kTileBytes = BR * D * 2;
-    constexpr int kStageBytes = 2 * kTileBytes + 2 * BR * 4;
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-
-    const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, l32 = lane & 31;
-    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, uniform
-    const int key_blocks = (p.n + BC - 1) / BC;
-    int bh, j;
-    decode_block(blockIdx.x, key_blocks, p.batch * p.heads, bh, j);
-    const long base = (long)(bh / p.heads) * p.stride_b + (long)(bh % p.heads) * p.stride_h;
-    const long ld = p.stride_n;
-    const int j0 = j * BC;
-    const float* lse_g = p.LSE + (long)bh * p.n;
-    const float* delta_g = p.delta + (long)bh * p.n;
-
-    // iteration space over 64-row query tiles
-    int n_it, t0 = 0, lp0 = 0;
-    if (p.list_ptr) {
-        lp0 = p.list_ptr[j];
-        n_it = (p.list_ptr[j + 1] - lp0) * (128 / BR);
-    } else {
-        t0 = p.causal ? j0 / BR : 0;
-        n_it = (p.n + BR - 1) / BR - t0;
-    }
-    auto tile_start = [&](int it) -> int {
-        if (p.list_ptr) return p.list_idx[lp0 + it / (128 / BR)] * 128 + (it % (128 / BR)) * BR;
-        return (t0 + it) * BR;
-    };
-
-    // resident K, V fragments
-    const int key = j0 + 32 * w + l32;
-    bf16x8 kf[KS], vf[KS];
-    {
-        const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            kf[ks] = zero;
-            vf[ks] = zero;
-            if (key < p.n) {
-                kf[ks] = *reinterpret_cast<const bf16x8*>(p.K + base + (long)key * ld + 16 * ks + 8 * h);
-                vf[ks] = *reinterpret_cast<const bf16x8*>(p.V + base + (long)key * ld + 16 * ks + 8 * h);
-            }
-        }
-    }
-
-    f32x16 dk[MT], dv[MT];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) { dk[mt][i] = 0.f; dv[mt][i] = 0.f; }
-
-    const float c = p.scale * kLog2e;
-    TileCopy<D, BR> cq, cdo;
-    float row_stat = 0.f;  // threads 0..63 stage lse2, 64..127 stage delta
-
-    auto fetch = [&](int i0) {
-        cq.fetch(p.Q + base, ld, i0, p.n, tid);
-        cdo.fetch(p.dO + base, ld, i0, p.n, tid);
-        if (tid < BR) {
-            const int q = i0 + tid;
-            row_stat = q < p.n ? lse_g[q] * kLog2e : __builtin_inff();
-        } else if (tid < 2 * BR) {
-            const int q = i0 + tid - BR;
-            row_stat = q < p.n ? delta_g[q] : 0.f;
-        }
-    };
-    auto commit = [&](int stage) {
-        char* s = smem + stage * kStageBytes;
-        cq.store(s, tid);
-        cdo.store(s + kTileBytes, tid);
-        if (tid < 2 * BR) reinterpret_cast<float*>(s + 2 * kTileBytes)[tid] = row_stat;
-    };
-
-    if (n_it > 0) {
-        fetch(tile_start(0));
-        commit(0);
-    }
-    __syncthreads();
-
-    for (int it = 0; it < n_it; ++it) {
-        const int i0 = tile_start(it);
-        const bool more = it + 1 < n_it;
-        if (more) fetch(tile_start(it + 1));
-
-        const char* qs = smem + (it & 1) * kStageBytes;
-        const char* dos = qs + kTileBytes;
-        const float* lse_s = reinterpret_cast<const float*>(qs + 2 * kTileBytes);
-        const float* delta_s = lse_s + BR;
-
-        // causal: a tile whose last query precedes this block's first key sees nothing
-        const bool skip = p.causal && (i0 + BR - 1 < j0);
-        if (!skip) {
-            f32x16 s[2], dp[2];
-#pragma unroll
-            for (int T = 0; T < 2; ++T)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) { s[T][i] = 0.f; dp[T][i] = 0.f; }
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-                for (int T = 0; T < 2; ++T) s[T] = mfma32(load_frag<D>(qs, 32 * T, ks, lane), kf[ks], s[T]);
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-                for (int T = 0; T < 2; ++T) dp[T] = mfma32(load_frag<D>(dos, 32 * T, ks, lane), vf[ks], dp[T]);
-
-            const bool need_mask = p.causal && (i0 < j0 + BC - 1);
-#pragma unroll
-            for (int T = 0; T < 2; ++T)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const f32x4 L = *reinterpret_cast<const f32x4*>(lse_s + 32 * T + 8 * g + 4 * h);
-                    const f32x4 Dl = *reinterpret_cast<const f32x4*>(delta_s + 32 * T + 8 * g + 4 * h);
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int i = 4 * g + r;
-                        float pv = __builtin_amdgcn_exp2f(s[T][i] * c - L[r]);
-                        if (need_mask && key > i0 + 32 * T + 8 * g + 4 * h + r) pv = 0.f;
-                        s[T][i] = pv;
-                        dp[T][i] = pv * (dp[T][i] - Dl[r]);
-                    }
-                }
-            bf16x8 pb[2][2], dsb[2][2];
-#pragma unroll
-            for (int T = 0; T < 2; ++T)
-#pragma unroll
-                for (int ss = 0; ss < 2; ++ss) {
-                    pb[T][ss] = acc_to_operand(s[T], ss);
-                    dsb[T][ss] = acc_to_operand(dp[T], ss);
-                }
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                for (int T = 0; T < 2; ++T)
-#pragma unroll
-                    for (int ss = 0; ss < 2; ++ss)
-                        dv[mt] = mfma32(load_frag_t<D>(dos, 32 * mt, 32 * T + 16 * ss, lane), pb[T][ss], dv[mt]);
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                for (int T = 0; T < 2; ++T)
-#pragma unroll
-                    for (int ss = 0; ss < 2; ++ss)
-                        dk[mt] = mfma32(load_frag_t<D>(qs, 32 * mt, 32 * T + 16 * ss, lane), dsb[T][ss], dk[mt]);
-        }
-        if (more) commit((it + 1) & 1);
-        __syncthreads();
-    }
-
-    // epilogue: accumulators hold dK^T, dV^T (register <-> d, lane <-> key)
-    if (key < p.n) {
-        __bf16* dk_row = p.dK + base + (long)key * ld;
-        __bf16* dv_row = p.dV + base + (long)key * ld;
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int col = 32 * mt + 8 * g + 4 * h;
-                u32x2 a, b;
-                a[0] = pack_bf16(dk[mt][4 * g + 0] * p.scale, dk[mt][4 * g + 1] * p.scale);
-                a[1] = pack_bf16(dk[mt][4 * g + 2] * p.scale, dk[mt][4 * g + 3] * p.scale);
-                b[0] = pack_bf16(dv[mt][4 * g + 0], dv[mt][4 * g + 1]);
-                b[1] = pack_bf16(dv[mt][4 * g + 2], dv[mt][4 * g + 3]);
-                *reinterpret_cast<u32x2*>(dk_row + col) = a;
-                *reinterpret_cast<u32x2*>(dv_row + col) = b;
-            }
-    }
-}
-
-// --------------------------------------------------------------- dK, dV, d = 128 variant
-// At d = 128 the layout above needs more than 256 registers per lane, which would leave one
-// wave per SIMD and nothing to hide latency behind.  This variant keeps two workgroups per CU:
-// a workgroup owns 64 keys and splits each (64 query x 64 key) tile twice over its 4 waves,
-//   phase 1: wave (wk, wx) computes S^T and dP^T for key half wk and query half wx (lane <->
-//            query), then P and dS go to LDS as bf16 tiles [query][key];
+// A workgroup owns 64 keys and streams 64-query tiles; per tile its 4 waves work in two phases:
+//   phase 1: wave (wk, wx) computes S^T and dP^T for key half wk and query half wx, with the
+//            resident K / V fragments as A operands (lane <-> query, so lse2 and delta are
+//            per-lane scalars), then P and dS go to LDS as bf16 tiles [query][key];
 //   phase 2: wave (wk, wx) accumulates dV^T (wx = 0) or dK^T (wx = 1) for the d-half wk and all
-//            64 keys over the 64 queries, as a 2 x 2 block of accumulators; P / dS (B operands)
-//            and dO^T / Q^T (A operands) are all read with transposing LDS loads, each fragment
-//            feeding two MFMAs.
+//            64 keys over the 64 queries, as a block of accumulators in which every fragment
+//            read from LDS feeds two MFMAs; P / dS (B operands) and dO^T / Q^T (A operands)
+//            are all read with transposing LDS loads.
+// Keeping K, V and both gradients of 128 keys in the registers of one workgroup instead (no LDS
+// round trip for P and dS) needs more than 256 registers per lane at d = 128, i.e. one wave per
+// SIMD; that variant was measured at 60 % of this one's speed at d = 128 and 91 % at d = 64.
 // Wave priorities per phase: the two waves that share a SIMD compete for one matrix pipe and
 // fall into step; ranking phase 1 above the exponentials above phase 2 lets one of them run ahead
 // (measured: 3-4 % faster).
 constexpr int kPrioPhase1 = 3, kPrioSoftmax = 1, kPrioPhase2 = 0;
 template <int D>
-__global__ void __launch_bounds__(kThreads, 2) bwd_dkdv_split_kernel(FusedParams p) {
+__global__ void __launch_bounds__(kThreads, 2) bwd_dkdv_kernel(FusedParams p) {
     constexpr int BR = 64, BC = 64, KS = D / 16, MT = D / 32;
     constexpr int kTileBytes = BR * D * 2;
     constexpr int kStageBytes = 2 * kTileBytes;
@@ -630,14 +453,9 @@ static hipError_t launch_bwd(const FusedParams& p, const int32_t* csr_ptr, const
     const int bh = p.batch * p.heads;
     launch_delta(p, D, stream);
 
-    constexpr bool kSplit = D == 128;
-    constexpr int kv_lds = kSplit ? 2 * (2 * 64 * D * 2) + 2 * 64 * 64 * 2 : 2 * (2 * 64 * D * 2 + 2 * 64 * 4);
+    constexpr int kv_lds = 2 * (2 * 64 * D * 2) + 2 * 64 * 64 * 2;  // two stages of Q, dO; P and dS
     constexpr int q_lds = 2 * (2 * 64 * D * 2);
-    const void* kv_fn;
-    if constexpr (kSplit)
-        kv_fn = reinterpret_cast<const void*>(bwd_dkdv_split_kernel<D>);
-    else
-        kv_fn = reinterpret_cast<const void*>(bwd_dkdv_kernel<D>);
+    const void* kv_fn = reinterpret_cast<const void*>(bwd_dkdv_kernel<D>);
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(kv_fn, hipFuncAttributeMaxDynamicSharedMemorySize, kv_lds);
@@ -651,11 +469,7 @@ static hipError_t launch_bwd(const FusedParams& p, const int32_t* csr_ptr, const
     FusedParams pk = p;
     pk.list_ptr = csc_ptr;
     pk.list_idx = csc_idx;
-    if constexpr (kSplit)
-        hipLaunchKernelGGL(bwd_dkdv_split_kernel<D>, dim3((unsigned)((p.n + 63) / 64 * bh)), dim3(kThreads), kv_lds,
-                           stream, pk);
-    else
-        hipLaunchKernelGGL(bwd_dkdv_kernel<D>, dim3((unsigned)(blocks128 * bh)), dim3(kThreads), kv_lds, stream, pk);
+    hipLaunchKernelGGL(bwd_dkdv_kernel<D>, dim3((unsigned)((p.n + 63) / 64 * bh)), dim3(kThreads), kv_lds, stream, pk);
     FusedParams pq = p;
     pq.list_ptr = csr_ptr;
     pq.list_idx = csr_idx;

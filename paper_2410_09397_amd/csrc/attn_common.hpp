@@ -147,36 +147,6 @@ __device__ __forceinline__ bf16x8 load_frag_perm(const char* tile, int row0, int
     return __builtin_bit_cast(bf16x8, r);
 }
 
-// Cooperative copy of a [ROWS x D] bf16 tile: global (row stride `ld` elements) -> registers
-// -> swizzled LDS tile.  Rows at or beyond `rows_valid` read as zero.
-template <int D, int ROWS>
-struct TileCopy {
-    static constexpr int kChunksPerRow = D / 8;
-    static constexpr int kPerThread = ROWS * kChunksPerRow / kThreads;
-    static_assert(ROWS * kChunksPerRow % kThreads == 0, "tile must split evenly over the workgroup");
-    u32x4 regs[kPerThread];
-
-    __device__ __forceinline__ void fetch(const __bf16* base, long ld, int row_begin, int rows_valid, int tid) {
-#pragma unroll
-        for (int u = 0; u < kPerThread; ++u) {
-            const int q = tid + u * kThreads;
-            const int row = q / kChunksPerRow, c = q % kChunksPerRow;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (row_begin + row < rows_valid)
-                v = *reinterpret_cast<const u32x4*>(base + (long)(row_begin + row) * ld + c * 8);
-            regs[u] = v;
-        }
-    }
-    __device__ __forceinline__ void store(char* tile, int tid) const {
-#pragma unroll
-        for (int u = 0; u < kPerThread; ++u) {
-            const int q = tid + u * kThreads;
-            const int row = q / kChunksPerRow, c = q % kChunksPerRow;
-            *reinterpret_cast<u32x4*>(tile + tile_off<D>(row, c)) = regs[u];
-        }
-    }
-};
-
 // Asynchronous copy of a [ROWS x D] bf16 tile from global memory straight into a swizzled LDS
 // tile (global_load_lds_dwordx4: no staging registers).  One instruction moves 1 KB per wave and
 // lands lane l's 16 bytes at LDS base + 16 l, so the lane that owns LDS position (row, chunk p)
