@@ -121,7 +121,7 @@ def main():
                    "causal": w.causal, "block_sparse": w.sparse, "step": "attn_fwd + attn_bwd"},
         "bwd_ms": bwd_ms, "fwd_ms": fwd_ms, "fwd_tflops": w.fwd_flops() / (fwd_ms * 1e-3) * 1e-12,
         "step_tflops": (w.fwd_flops() + w.bwd_flops()) / (ms_per_step * 1e-3) * 1e-12,
-        "roofline": {"bound": "mfma" if w.dtype == "bf16" else "alu", "kernel": "attn_bwd (delta + dK/dV + dQ kernels)",
+        "roofline": {"bound": "mfma" if w.dtype == "bf16" else "alu", "kernel": "attn_bwd (all kernels of one call)",
                      "achieved": bwd_tflops, "peak": peak, "unit": "TFLOP/s", "frac": bwd_tflops / peak,
                      "traffic": traffic},
         "io_bound": bound,

@@ -300,7 +300,22 @@ __global__ void __launch_bounds__(kThreads, QT == 1 ? 2 : 1) bwd_dq_kernel(Fused
             }
         }
         lse2[t] = ok ? p.LSE[(long)bh * p.n + q[t]] * kLog2e : __builtin_inff();
-        dl[t] = ok ? p.delta[(long)bh * p.n + q[t]] : 0.f;
+        // delta = rowsum(dO o O) of this lane's query: the dO fragments are at hand, the O row is
+        // read once here (and nowhere else in the backward); the two lane halves hold the two
+        // halves of every 16-element chunk.  The dK / dV kernel, which runs after this one,
+        // takes delta from the workspace.
+        float dsum = 0.f;
+        if (ok) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const bf16x8 of = *reinterpret_cast<const bf16x8*>(p.O + base + (long)q[t] * ld + 16 * ks + 8 * h);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) dsum += (float)of[e] * (float)gf[t][ks][e];
+            }
+        }
+        dsum += __shfl_xor(dsum, 32, 64);
+        dl[t] = ok ? dsum : 0.f;
+        if (ok && h == 0) p.delta[(long)bh * p.n + q[t]] = dsum;
     }
 
     f32x16 dq[QT][MT];
@@ -451,7 +466,6 @@ template <int D>
 static hipError_t launch_bwd(const FusedParams& p, const int32_t* csr_ptr, const int32_t* csr_idx,
                              const int32_t* csc_ptr, const int32_t* csc_idx, hipStream_t stream) {
     const int bh = p.batch * p.heads;
-    launch_delta(p, D, stream);
 
     constexpr int kv_lds = 2 * (2 * 64 * D * 2) + 2 * 64 * 64 * 2;  // two stages of Q, dO; P and dS
     constexpr int q_lds = 2 * (2 * 64 * D * 2);
@@ -466,10 +480,6 @@ static hipError_t launch_bwd(const FusedParams& p, const int32_t* csr_ptr, const
         configured = true;
     }
     const int blocks128 = (p.n + 127) / 128;
-    FusedParams pk = p;
-    pk.list_ptr = csc_ptr;
-    pk.list_idx = csc_idx;
-    hipLaunchKernelGGL(bwd_dkdv_kernel<D>, dim3((unsigned)((p.n + 63) / 64 * bh)), dim3(kThreads), kv_lds, stream, pk);
     FusedParams pq = p;
     pq.list_ptr = csr_ptr;
     pq.list_idx = csr_idx;
@@ -477,6 +487,10 @@ static hipError_t launch_bwd(const FusedParams& p, const int32_t* csr_ptr, const
     // LDS fragment feeding two MFMAs, halves the LDS traffic but measured 20 % slower at d = 128:
     // with a single wave per SIMD the softmax arithmetic no longer overlaps another wave's MFMAs.)
     hipLaunchKernelGGL((bwd_dq_kernel<D, 1>), dim3((unsigned)(blocks128 * bh)), dim3(kThreads), q_lds, stream, pq);
+    FusedParams pk = p;
+    pk.list_ptr = csc_ptr;
+    pk.list_idx = csc_idx;
+    hipLaunchKernelGGL(bwd_dkdv_kernel<D>, dim3((unsigned)((p.n + 63) / 64 * bh)), dim3(kThreads), kv_lds, stream, pk);
     return hipGetLastError();
 }
 
