@@ -17,38 +17,6 @@ namespace attn {
 
 namespace {
 
-constexpr uint32_t kRsrcFlags = 0x00020000;  // raw buffer, 32-bit data format
-
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, kRsrcFlags);
-}
-
-// Cooperative copy of a [ROWS x COLS] bf16 tile through registers into a swizzled LDS tile.
-// Buffer loads return zero beyond the resource's size, so ragged edges need no branches.
-template <int COLS, int ROWS>
-struct BufTile {
-    static constexpr int kCPR = COLS / 8;
-    static constexpr int kPer = ROWS * kCPR / kThreads;
-    static_assert(ROWS * kCPR % kThreads == 0, "tile must split evenly over the workgroup");
-    u32x4 regs[kPer];
-    __device__ __forceinline__ void fetch(__amdgpu_buffer_rsrc_t r, uint32_t row0, uint32_t col0, uint32_t ld_bytes,
-                                          int tid) {
-#pragma unroll
-        for (int u = 0; u < kPer; ++u) {
-            const int q = tid + u * kThreads;
-            const uint32_t row = q / kCPR, c = q % kCPR;
-            regs[u] = __builtin_amdgcn_raw_buffer_load_b128(r, (row0 + row) * ld_bytes + (col0 + 8 * c) * 2, 0, 0);
-        }
-    }
-    __device__ __forceinline__ void store(char* tile, int tid) const {
-#pragma unroll
-        for (int u = 0; u < kPer; ++u) {
-            const int q = tid + u * kThreads;
-            *reinterpret_cast<u32x4*>(tile + tile_off<COLS>(q / kCPR, q % kCPR)) = regs[u];
-        }
-    }
-};
-
 __device__ __forceinline__ void zero_acc(f32x16 (&c)[2][2]) {
 #pragma unroll
     for (int a = 0; a < 2; ++a)
@@ -69,7 +37,7 @@ __global__ void __launch_bounds__(kThreads, 2) ld_scores_kernel(LargeDParams p) 
     constexpr int BK = 32;
     constexpr int kTile = 128 * BK * 2;                       // bytes per operand tile
     constexpr int kOps = MODE == kBackward ? 4 : 2;           // K, Q (+ V, dO)
-    extern __shared__ __attribute__((aligned(16))) char smem[];
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
     const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, l32 = lane & 31;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, uniform
     const int wm = w >> 1, wn = w & 1;
@@ -95,41 +63,35 @@ __global__ void __launch_bounds__(kThreads, 2) ld_scores_kernel(LargeDParams p) 
     }
     if (p.causal && kb > qb) return;  // whole tile above the diagonal: never read downstream
     const long base = (long)(bh / p.heads) * p.stride_b + (long)(bh % p.heads) * p.stride_h;
-    const uint32_t ldb = (uint32_t)p.stride_n * 2;
-    const uint32_t bytes = (uint32_t)(((long)(p.n - 1) * p.stride_n + p.d) * 2);
-    const auto rK = make_rsrc(p.K + base, bytes), rQ = make_rsrc(p.Q + base, bytes);
-    const auto rV = make_rsrc(MODE == kBackward ? p.V + base : p.K + base, bytes);
-    const auto rG = make_rsrc(MODE == kBackward ? p.dO + base : p.Q + base, bytes);
     const int k0 = kb * 128, q0 = qb * 128;
+    const __bf16* gK = p.K + base;
+    const __bf16* gQ = p.Q + base;
+    const __bf16* gV = (MODE == kBackward ? p.V : p.K) + base;
+    const __bf16* gG = (MODE == kBackward ? p.dO : p.Q) + base;
+    const long ld = p.stride_n;
 
     f32x16 s[2][2], dp[2][2];
     zero_acc(s);
     if (MODE == kBackward) zero_acc(dp);
 
-    BufTile<BK, 128> tk, tq, tv, tg;
-    auto fetch = [&](int c0) {
-        tk.fetch(rK, k0, c0, ldb, tid);
-        tq.fetch(rQ, q0, c0, ldb, tid);
-        if (MODE == kBackward) {
-            tv.fetch(rV, k0, c0, ldb, tid);
-            tg.fetch(rG, q0, c0, ldb, tid);
-        }
-    };
-    auto commit = [&](int stage) {
+    // Operand chunks (128 rows x BK columns each) go straight from global memory into the LDS
+    // stage that was last read one chunk ago; rows past n repeat the last row and are masked in
+    // the epilogue.
+    auto fetch = [&](int c0, int stage) {
         char* b = smem + stage * kOps * kTile;
-        tk.store(b, tid);
-        tq.store(b + kTile, tid);
+        load_tile_direct<BK, 128>(gK + c0, ld, k0, p.n, b, tid);
+        load_tile_direct<BK, 128>(gQ + c0, ld, q0, p.n, b + kTile, tid);
         if (MODE == kBackward) {
-            tv.store(b + 2 * kTile, tid);
-            tg.store(b + 3 * kTile, tid);
+            load_tile_direct<BK, 128>(gV + c0, ld, k0, p.n, b + 2 * kTile, tid);
+            load_tile_direct<BK, 128>(gG + c0, ld, q0, p.n, b + 3 * kTile, tid);
         }
     };
     const int chunks = p.d / BK;
-    fetch(0);
-    commit(0);
+    fetch(0, 0);
+    wait_direct_loads();
     __syncthreads();
     for (int kc = 0; kc < chunks; ++kc) {
-        if (kc + 1 < chunks) fetch((kc + 1) * BK);
+        if (kc + 1 < chunks) fetch((kc + 1) * BK, (kc + 1) & 1);
         const char* b = smem + (kc & 1) * kOps * kTile;
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
@@ -155,7 +117,7 @@ __global__ void __launch_bounds__(kThreads, 2) ld_scores_kernel(LargeDParams p) 
                     for (int tn = 0; tn < 2; ++tn) dp[tm][tn] = mfma32(a[tm], q[tn], dp[tm][tn]);
             }
         }
-        if (kc + 1 < chunks) commit((kc + 1) & 1);
+        wait_direct_loads();
         __syncthreads();
     }
 
@@ -257,11 +219,13 @@ struct GemmArgs {
     float alpha;
 };
 
+// k-step of the product kernel: 32 keeps four workgroups per CU resident (32 KB of LDS each)
+constexpr int kGemmBK = 32;
 template <bool A_KMAJOR>
 __global__ void __launch_bounds__(kThreads, 2) ld_gemm_kernel(LargeDParams p, GemmArgs g) {
-    constexpr int BK = 64;
+    constexpr int BK = kGemmBK;
     constexpr int kTile = 128 * BK * 2;
-    extern __shared__ __attribute__((aligned(16))) char smem[];
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
     const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, l32 = lane & 31;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, uniform
     const int wm = w >> 1, wn = w & 1;
@@ -278,9 +242,8 @@ __global__ void __launch_bounds__(kThreads, 2) ld_gemm_kernel(LargeDParams p, Ge
     }
     const int m0 = mb * 128;
     const long base = (long)(bh / p.heads) * p.stride_b + (long)(bh % p.heads) * p.stride_h;
-    const auto rA = make_rsrc(g.A + (long)bh * p.npad * p.npad, (uint32_t)((long)p.npad * p.npad * 2));
-    const auto rB = make_rsrc(g.B + base, (uint32_t)(((long)(p.n - 1) * p.stride_n + p.d) * 2));
-    const uint32_t lda = (uint32_t)p.npad * 2, ldb = (uint32_t)p.stride_n * 2;
+    const __bf16* gA = g.A + (long)bh * p.npad * p.npad;  // npad x npad, zero beyond n
+    const __bf16* gB = g.B + base;
     int k_begin = 0, k_end = p.npad;
     if (p.causal) {
         if (A_KMAJOR) k_begin = m0;   // queries at or after this key block
@@ -289,23 +252,21 @@ __global__ void __launch_bounds__(kThreads, 2) ld_gemm_kernel(LargeDParams p, Ge
 
     f32x16 c[2][2];
     zero_acc(c);
-    BufTile<A_KMAJOR ? 128 : BK, A_KMAJOR ? BK : 128> ta;
-    BufTile<128, BK> tb;
-    auto fetch = [&](int k) {
-        if (A_KMAJOR) ta.fetch(rA, k, m0, lda, tid);
-        else ta.fetch(rA, m0, k, lda, tid);
-        tb.fetch(rB, k, n0, ldb, tid);
+    // Operand tiles go straight from global memory into the LDS stage that was last read one
+    // step ago.  Rows of B past n repeat the last row; they meet columns (rows, if A is read
+    // transposed) of A that are zero.
+    auto fetch = [&](int k, int stage) {
+        char* at = smem + stage * 2 * kTile;
+        if (A_KMAJOR) load_tile_direct<128, BK>(gA + m0, p.npad, k, p.npad, at, tid);
+        else load_tile_direct<BK, 128>(gA + k, p.npad, m0, p.npad, at, tid);
+        load_tile_direct<128, BK>(gB + n0, p.stride_n, k, p.n, at + kTile, tid);
     };
-    auto commit = [&](int stage) {
-        ta.store(smem + stage * 2 * kTile, tid);
-        tb.store(smem + stage * 2 * kTile + kTile, tid);
-    };
-    fetch(k_begin);
-    commit(0);
+    fetch(k_begin, 0);
+    wait_direct_loads();
     __syncthreads();
     int stage = 0;
     for (int k = k_begin; k < k_end; k += BK, stage ^= 1) {
-        if (k + BK < k_end) fetch(k + BK);
+        if (k + BK < k_end) fetch(k + BK, stage ^ 1);
         const char* at = smem + stage * 2 * kTile;
         const char* bt = at + kTile;
 #pragma unroll
@@ -322,7 +283,7 @@ __global__ void __launch_bounds__(kThreads, 2) ld_gemm_kernel(LargeDParams p, Ge
 #pragma unroll
                 for (int tn = 0; tn < 2; ++tn) c[tm][tn] = mfma32(a[tm], b[tn], c[tm][tn]);
         }
-        if (k + BK < k_end) commit(stage ^ 1);
+        wait_direct_loads();
         __syncthreads();
     }
     // accumulator: lane <-> output column, register <-> output row
@@ -348,7 +309,7 @@ static void run_gemm(const LargeDParams& p, const __bf16* A, const __bf16* B, __
                      hipStream_t stream) {
     const dim3 grid((unsigned)(((p.d + 127) / 128) * (p.npad / 128) * p.batch * p.heads));
     GemmArgs g{A, B, C, alpha};
-    hipLaunchKernelGGL(ld_gemm_kernel<A_KMAJOR>, grid, dim3(kThreads), 2 * 2 * 128 * 64 * 2, stream, p, g);
+    hipLaunchKernelGGL(ld_gemm_kernel<A_KMAJOR>, grid, dim3(kThreads), 2 * 2 * 128 * kGemmBK * 2, stream, p, g);
 }
 
 hipError_t launch_larged(bool backward, const LargeDParams& p, hipStream_t stream) {
@@ -357,8 +318,8 @@ hipError_t launch_larged(bool backward, const LargeDParams& p, hipStream_t strea
         hipError_t e = set_lds(reinterpret_cast<const void*>(ld_scores_kernel<kStats>), 2 * 2 * 128 * 32 * 2);
         if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_scores_kernel<kProbs>), 2 * 2 * 128 * 32 * 2);
         if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_scores_kernel<kBackward>), 2 * 4 * 128 * 32 * 2);
-        if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_gemm_kernel<true>), 2 * 2 * 128 * 64 * 2);
-        if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_gemm_kernel<false>), 2 * 2 * 128 * 64 * 2);
+        if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_gemm_kernel<true>), 2 * 2 * 128 * kGemmBK * 2);
+        if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_gemm_kernel<false>), 2 * 2 * 128 * kGemmBK * 2);
         if (e != hipSuccess) return e;
         configured = true;
     }
