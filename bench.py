@@ -58,6 +58,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", type=int, default=3, help="1..5, index into the metric's configurations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--wgrad", action="store_true",
+                    help="also time attn_bwd_wgrad (the paper's weight gradient) on the same shape and "
+                         "report it in an extra \"wgrad\" object (bf16, d <= 128, no block mask only)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy, so that HBM byte counters read in the "
                          "same profiler run can be scaled by a transfer of known size")
@@ -127,6 +130,27 @@ def main():
         "io_bound": bound,
         "traffic_over_yardstick": (traffic / bound["yardstick_bytes"]) if traffic else None,
     }
+    if args.wgrad and w.dtype == "bf16" and w.d in (64, 128) and not w.sparse:
+        del grads, O, ws
+        wi = synth.make_wgrad_inputs(w)
+        A1, A2, A3, X, Y, G = (torch.from_numpy(wi[t]).to("cuda").to(dt) for t in ("A1", "A2", "A3", "X", "Y", "dO"))
+        g = torch.empty((w.batch, w.heads, w.d, w.d), dtype=torch.float32, device="cuda")
+        wws = torch.empty(attn.attn_wgrad_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+        for _ in range(args.warmup):
+            attn.attn_bwd_wgrad(A1, A2, A3, X, Y, G, scale=1.0, causal=w.causal, out=g, workspace=wws)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            attn.attn_bwd_wgrad(A1, A2, A3, X, Y, G, scale=1.0, causal=w.causal, out=g, workspace=wws)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        # the paper's algorithm: A = S A_2^T, q = dO h^T, T = A_1^T p (n x n x d each, over visible pairs) and
+        # S = A_1 X, h = A_3 Y, g = T A_2 (n x d x d each)
+        bh = w.batch * w.heads
+        flops = bh * (6.0 * w.n * w.n * w.d * w.kept_fraction() + 6.0 * w.n * w.d * w.d)
+        out["wgrad"] = {"ms": ms, "algorithmic_tflops": flops / (ms * 1e-3) * 1e-12,
+                        "note": "projections + forward + dQ kernel + A_1^T dQ; executes 10 n^2 d per pair"}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))

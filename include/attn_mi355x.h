@@ -97,6 +97,25 @@ attn_status attn_bwd_blocksparse(const attn_desc *desc, const attn_blockmask *ma
                                  const void *dO, const float *LSE, void *dQ, void *dK, void *dV,
                                  void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Weight gradient of the paper's loss (Def. 3.2 and the backward gradient of Sec. 3.1; the
+ * no-cache algorithm of App. C.1 states the same product step by step): with
+ *     S = A_1 X (queries), A_2 (keys), h = A_3 Y (values), f, q, p as above,
+ *     g = dL/dX = scale * A_1^T p A_2            one d x d matrix per (batch, head), float32.
+ * A_1, A_2, A_3 and dO are [batch, heads, n, d] (here contiguous: stride_n == d, stride_h ==
+ * n * d, stride_b == heads * n * d), X and Y are contiguous [batch, heads, d, d], row-major
+ * (X[k][c]: input feature k, output feature c), g is contiguous [batch, heads, d, d].  dO is the
+ * gradient of the loss with respect to the attention output (the paper's O - E).
+ * The two projections, the forward, the dQ part of the backward and the product A_1^T dQ all run
+ * on the device; queries, values, O and dQ pass through the workspace in bf16.
+ * Supported: ATTN_BF16, d in {64, 128}, no block mask; anything else -> ATTN_ERR_UNSUPPORTED.
+ * attn_wgrad_workspace_bytes returns 0 for an invalid or unsupported desc.
+ */
+size_t attn_wgrad_workspace_bytes(const attn_desc *desc);
+attn_status attn_bwd_wgrad(const attn_desc *desc, const void *A1, const void *A2, const void *A3,
+                           const void *X, const void *Y, const void *dO, float *g,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
 /* Checks HOST copies of a block mask: monotone pointers, strictly ascending in-range indices,
  * nblk == ceil(n / block), and that the two orientations hold the same pairs. */
 attn_status attn_blockmask_validate(int32_t block, int32_t nblk, int32_t n,

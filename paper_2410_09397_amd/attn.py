@@ -17,7 +17,7 @@ ATTN_OK, ATTN_ERR_INVALID_ARG, ATTN_ERR_UNSUPPORTED, ATTN_ERR_WORKSPACE, ATTN_ER
 ATTN_F32, ATTN_BF16 = 0, 1
 
 EXPORTS = ("attn_workspace_bytes", "attn_fwd", "attn_bwd", "attn_bwd_blocksparse",
-           "attn_blockmask_validate", "attn_status_str")
+           "attn_wgrad_workspace_bytes", "attn_bwd_wgrad", "attn_blockmask_validate", "attn_status_str")
 
 
 class attn_desc(ctypes.Structure):
@@ -59,6 +59,10 @@ def lib():
         L.attn_bwd.argtypes = [dp] + [vp] * 9 + [vp, ctypes.c_size_t, vp]
         L.attn_bwd_blocksparse.restype = ctypes.c_int
         L.attn_bwd_blocksparse.argtypes = [dp, mp] + [vp] * 9 + [vp, ctypes.c_size_t, vp]
+        L.attn_wgrad_workspace_bytes.restype = ctypes.c_size_t
+        L.attn_wgrad_workspace_bytes.argtypes = [dp]
+        L.attn_bwd_wgrad.restype = ctypes.c_int
+        L.attn_bwd_wgrad.argtypes = [dp] + [vp] * 7 + [vp, ctypes.c_size_t, vp]
         L.attn_blockmask_validate.restype = ctypes.c_int
         L.attn_blockmask_validate.argtypes = [ctypes.c_int32] * 3 + [i32p] * 4
         L.attn_status_str.restype = ctypes.c_char_p
@@ -184,3 +188,27 @@ def attn_bwd(Q, K, V, O, dO, LSE, scale, causal=False, stream=None, out=None, wo
 def attn_bwd_blocksparse(Q, K, V, O, dO, LSE, scale, mask, causal=False, stream=None, out=None, workspace=None):
     """dQ, dK, dV under a BlockMask."""
     return _bwd("attn_bwd_blocksparse", Q, K, V, O, dO, LSE, scale, causal, mask, stream, out, workspace)
+
+
+def attn_wgrad_workspace_bytes(desc):
+    return lib().attn_wgrad_workspace_bytes(ctypes.byref(desc))
+
+
+def attn_bwd_wgrad(A1, A2, A3, X, Y, dO, scale=1.0, causal=False, stream=None, out=None, workspace=None):
+    """g = dL/dX [batch, heads, d, d] (float32) of the paper's loss: queries A1 X, keys A2, values A3 Y."""
+    import torch
+    _same_layout(A1, A2, A3, dO)
+    _same_layout(X, Y)
+    desc = _desc(A1, scale, causal)
+    b, h, n, d = A1.shape
+    if tuple(X.shape) != (b, h, d, d) or not X.is_contiguous() or not Y.is_contiguous() or X.dtype != A1.dtype:
+        raise ValueError("X and Y must be contiguous [batch, heads, d, d] tensors of the inputs' dtype")
+    g = out if out is not None else torch.empty((b, h, d, d), dtype=torch.float32, device=A1.device)
+    if workspace is None:
+        workspace = torch.empty(max(attn_wgrad_workspace_bytes(desc), 256), dtype=torch.uint8, device=A1.device)
+    st = lib().attn_bwd_wgrad(ctypes.byref(desc), A1.data_ptr(), A2.data_ptr(), A3.data_ptr(), X.data_ptr(),
+                              Y.data_ptr(), dO.data_ptr(), g.data_ptr(), workspace.data_ptr(), workspace.numel(),
+                              _stream(stream))
+    if st != ATTN_OK:
+        raise AttnError(st, "attn_bwd_wgrad")
+    return g

@@ -185,6 +185,36 @@ attn_status bwd_impl(const attn_desc* desc, const attn_blockmask* mask, const vo
     return e == hipSuccess ? ATTN_OK : ATTN_ERR_DEVICE;
 }
 
+// Weight-gradient entry point: bf16, d in {64, 128}, contiguous [batch, heads, n, d] tensors.
+attn_status wgrad_check(const attn_desc* d) {
+    const attn_status st = check_desc(d);
+    if (st != ATTN_OK) return st;
+    if (d->dtype != ATTN_BF16 || (d->d != 64 && d->d != 128)) return ATTN_ERR_UNSUPPORTED;
+    if (!is_empty(d) && (d->stride_n != d->d || d->stride_h != (int64_t)d->n * d->d ||
+                         d->stride_b != (int64_t)d->heads * d->n * d->d))
+        return ATTN_ERR_UNSUPPORTED;
+    return ATTN_OK;
+}
+
+// Workspace of the weight gradient: [Q][V][O][dQ] bf16 tensors, [LSE][delta] rows, [partial products].
+struct WgradLayout {
+    size_t q, v, o, dq, lse, delta, partial, total;
+};
+WgradLayout wgrad_layout(const attn_desc* d) {
+    const size_t bh = (size_t)d->batch * d->heads;
+    const size_t t = round_up(bh * d->n * d->d * 2, 256), r = round_up(bh * d->n * sizeof(float), 256);
+    WgradLayout l;
+    l.q = 0;
+    l.v = t;
+    l.o = 2 * t;
+    l.dq = 3 * t;
+    l.lse = 4 * t;
+    l.delta = 4 * t + r;
+    l.partial = 4 * t + 2 * r;
+    l.total = l.partial + round_up(bh * attn::wgrad_chunks(d->n) * d->d * d->d * sizeof(float), 256);
+    return l;
+}
+
 }  // namespace
 
 #pragma GCC visibility push(default)
@@ -268,6 +298,57 @@ attn_status attn_bwd_blocksparse(const attn_desc* desc, const attn_blockmask* ma
                                  void* stream) {
     if (!mask) return ATTN_ERR_INVALID_ARG;
     return bwd_impl(desc, mask, Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, stream);
+}
+
+size_t attn_wgrad_workspace_bytes(const attn_desc* desc) {
+    if (wgrad_check(desc) != ATTN_OK) return 0;
+    if (is_empty(desc)) return 256;
+    const WgradLayout l = wgrad_layout(desc);
+    return l.total;
+}
+
+attn_status attn_bwd_wgrad(const attn_desc* desc, const void* A1, const void* A2, const void* A3, const void* X,
+                           const void* Y, const void* dO, float* g, void* workspace, size_t workspace_bytes,
+                           void* stream) {
+    attn_status st = wgrad_check(desc);
+    if (st != ATTN_OK) return st;
+    if ((long)desc->batch * desc->heads == 0) return ATTN_OK;
+    if (desc->n == 0) {  // a sum over no rows: g = 0
+        if (!g || !aligned16(g)) return ATTN_ERR_INVALID_ARG;
+        const hipError_t e0 = attn::launch_wgrad_zero(desc->d, desc->batch * desc->heads, g,
+                                                      static_cast<hipStream_t>(stream));
+        return e0 == hipSuccess ? ATTN_OK : ATTN_ERR_DEVICE;
+    }
+    if (!A1 || !A2 || !A3 || !X || !Y || !dO || !g) return ATTN_ERR_INVALID_ARG;
+    if (!(aligned16(A1) && aligned16(A2) && aligned16(A3) && aligned16(X) && aligned16(Y) && aligned16(dO) &&
+          aligned16(g)))
+        return ATTN_ERR_INVALID_ARG;
+    const WgradLayout l = wgrad_layout(desc);
+    if (!workspace || workspace_bytes < l.total || !aligned16(workspace)) return ATTN_ERR_WORKSPACE;
+    char* ws = static_cast<char*>(workspace);
+    attn::WgradParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.A1 = static_cast<const __bf16*>(A1);
+    p.A2 = static_cast<const __bf16*>(A2);
+    p.A3 = static_cast<const __bf16*>(A3);
+    p.X = static_cast<const __bf16*>(X);
+    p.Y = static_cast<const __bf16*>(Y);
+    p.dO = static_cast<const __bf16*>(dO);
+    p.g = g;
+    p.Q = reinterpret_cast<__bf16*>(ws + l.q);
+    p.V = reinterpret_cast<__bf16*>(ws + l.v);
+    p.O = reinterpret_cast<__bf16*>(ws + l.o);
+    p.dQ = reinterpret_cast<__bf16*>(ws + l.dq);
+    p.LSE = reinterpret_cast<float*>(ws + l.lse);
+    p.delta = reinterpret_cast<float*>(ws + l.delta);
+    p.partial = reinterpret_cast<float*>(ws + l.partial);
+    p.batch = desc->batch;
+    p.heads = desc->heads;
+    p.n = desc->n;
+    p.scale = desc->scale;
+    p.causal = desc->causal;
+    const hipError_t e = attn::launch_wgrad_fused(desc->d, p, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ATTN_OK : ATTN_ERR_DEVICE;
 }
 
 attn_status attn_blockmask_validate(int32_t block, int32_t nblk, int32_t n, const int32_t* row_ptr,

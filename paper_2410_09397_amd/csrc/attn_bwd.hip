@@ -464,7 +464,7 @@ void launch_delta(const FusedParams& p, int d, hipStream_t stream) {
 
 template <int D>
 static hipError_t launch_bwd(const FusedParams& p, const int32_t* csr_ptr, const int32_t* csr_idx,
-                             const int32_t* csc_ptr, const int32_t* csc_idx, hipStream_t stream) {
+                             const int32_t* csc_ptr, const int32_t* csc_idx, hipStream_t stream, bool dq_only) {
     const int bh = p.batch * p.heads;
 
     constexpr int kv_lds = 2 * (2 * 64 * D * 2) + 2 * 64 * 64 * 2;  // two stages of Q, dO; P and dS
@@ -487,6 +487,7 @@ static hipError_t launch_bwd(const FusedParams& p, const int32_t* csr_ptr, const
     // LDS fragment feeding two MFMAs, halves the LDS traffic but measured 20 % slower at d = 128:
     // with a single wave per SIMD the softmax arithmetic no longer overlaps another wave's MFMAs.)
     hipLaunchKernelGGL((bwd_dq_kernel<D, 1>), dim3((unsigned)(blocks128 * bh)), dim3(kThreads), q_lds, stream, pq);
+    if (dq_only) return hipGetLastError();
     FusedParams pk = p;
     pk.list_ptr = csc_ptr;
     pk.list_idx = csc_idx;
@@ -495,10 +496,10 @@ static hipError_t launch_bwd(const FusedParams& p, const int32_t* csr_ptr, const
 }
 
 hipError_t launch_bwd_fused(int d, const FusedParams& p, const int32_t* csr_ptr, const int32_t* csr_idx,
-                            const int32_t* csc_ptr, const int32_t* csc_idx, hipStream_t stream) {
+                            const int32_t* csc_ptr, const int32_t* csc_idx, hipStream_t stream, bool dq_only) {
     switch (d) {
-        case 64: return launch_bwd<64>(p, csr_ptr, csr_idx, csc_ptr, csc_idx, stream);
-        case 128: return launch_bwd<128>(p, csr_ptr, csr_idx, csc_ptr, csc_idx, stream);
+        case 64: return launch_bwd<64>(p, csr_ptr, csr_idx, csc_ptr, csc_idx, stream, dq_only);
+        case 128: return launch_bwd<128>(p, csr_ptr, csr_idx, csc_ptr, csc_idx, stream, dq_only);
         default: return hipErrorInvalidValue;
     }
 }

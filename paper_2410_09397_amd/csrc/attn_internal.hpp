@@ -9,8 +9,10 @@ namespace attn {
 // Fused bf16 paths, d in {64, 128}.  csr_* / csc_* are device pointers or nullptr (dense).
 hipError_t launch_fwd_fused(int d, const FusedParams& p, const int32_t* csr_ptr, const int32_t* csr_idx,
                             hipStream_t stream);
+// dq_only: run the query-owner kernel alone (dQ and delta), for callers that need neither dK nor dV.
 hipError_t launch_bwd_fused(int d, const FusedParams& p, const int32_t* csr_ptr, const int32_t* csr_idx,
-                            const int32_t* csc_ptr, const int32_t* csc_idx, hipStream_t stream);
+                            const int32_t* csc_ptr, const int32_t* csc_idx, hipStream_t stream,
+                            bool dq_only = false);
 
 // delta[b, h, i] = sum_k dO_ik O_ik for bf16 tensors (p.O, p.dO, p.delta), any d % 8 == 0.
 void launch_delta(const FusedParams& p, int d, hipStream_t stream);
@@ -47,5 +49,21 @@ struct GenericParams {
     int block;
 };
 hipError_t launch_generic(bool is_bf16, bool backward, const GenericParams& p, hipStream_t stream);
+
+// Weight gradient g = A_1^T dQ of the paper's loss (bf16, d in {64, 128}, contiguous tensors).
+// Q, V, O, dQ are [b, h, n, d] bf16 scratch, LSE and delta [b, h, n] fp32, partial
+// [b * h, wgrad_chunks(n), d, d] fp32; X, Y are [b, h, d, d] bf16, g is [b, h, d, d] fp32.
+struct WgradParams {
+    const __bf16 *A1, *A2, *A3, *X, *Y, *dO;
+    float* g;
+    __bf16 *Q, *V, *O, *dQ;
+    float *LSE, *delta, *partial;
+    int batch, heads, n;
+    float scale;
+    int causal;
+};
+int wgrad_chunks(int n);
+hipError_t launch_wgrad_fused(int d, const WgradParams& p, hipStream_t stream);
+hipError_t launch_wgrad_zero(int d, int bh, float* g, hipStream_t stream);  // n == 0: g = 0
 
 }  // namespace attn

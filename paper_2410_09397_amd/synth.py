@@ -11,7 +11,7 @@ from dataclasses import dataclass, replace
 import numpy as np
 
 BASE_SEED = 241009397
-TENSOR_IDS = {"Q": 0, "K": 1, "V": 2, "dO": 3, "mask": 4}
+TENSOR_IDS = {"Q": 0, "K": 1, "V": 2, "dO": 3, "mask": 4, "A1": 5, "A2": 6, "A3": 7, "X": 8, "Y": 9}
 
 
 @dataclass(frozen=True)
@@ -116,4 +116,17 @@ def make_inputs(w, seed=BASE_SEED):
     out = {t: normal(shape, w.dO_std if t == "dO" else 1.0, seed, w.index, t, w.dtype)
            for t in ("Q", "K", "V", "dO")}
     out["keep"] = block_mask(w.nblk, w.extra_blocks, seed, w.index) if w.sparse else None
+    return out
+
+
+def make_wgrad_inputs(w, seed=BASE_SEED):
+    """Inputs of the weight-gradient entry point: A1, A2, A3, dO [batch, heads, n, d] ~ N(0, 1)
+    (dO with the workload's std), X [batch, heads, d, d] ~ N(0, 1 / d^2) so that the scores
+    <A1 X, A2> have unit variance without a 1/sqrt(d) factor, and Y ~ N(0, 1 / d) so that the values
+    A3 Y do.  float32 arrays holding storage-dtype values."""
+    shape, wshape = (w.batch, w.heads, w.n, w.d), (w.batch, w.heads, w.d, w.d)
+    out = {t: normal(shape, 1.0, seed, w.index, t, w.dtype) for t in ("A1", "A2", "A3")}
+    out["dO"] = normal(shape, w.dO_std, seed, w.index, "dO", w.dtype)
+    out["X"] = normal(wshape, 1.0 / w.d, seed, w.index, "X", w.dtype)
+    out["Y"] = normal(wshape, w.d ** -0.5, seed, w.index, "Y", w.dtype)
     return out

@@ -88,6 +88,30 @@ def test_null_and_misaligned_pointers_and_workspace():
     assert call_fwd(d, mask=ctypes.byref(m)) == attn.ATTN_ERR_INVALID_ARG
 
 
+def call_wgrad(d, ptrs=(P,) * 7, ws=P, ws_bytes=1 << 40):
+    return attn.lib().attn_bwd_wgrad(ctypes.byref(d) if d is not None else None, *ptrs, ws, ws_bytes, None)
+
+
+def test_wgrad_entry_point_validates_before_launch():
+    L = attn.lib()
+    d = desc()
+    need = L.attn_wgrad_workspace_bytes(ctypes.byref(d))
+    # Q, V, O, dQ in bf16, LSE and delta rows, one chunk of partial products
+    assert need >= 4 * 128 * 64 * 2 + 2 * 128 * 4 + 64 * 64 * 4
+    assert call_wgrad(None) == attn.ATTN_ERR_INVALID_ARG
+    assert call_wgrad(d, ptrs=(P, P, P, None, P, P, P)) == attn.ATTN_ERR_INVALID_ARG
+    assert call_wgrad(d, ptrs=(P, P, P, P, P, P + 4, P)) == attn.ATTN_ERR_INVALID_ARG
+    assert call_wgrad(d, ws=None) == attn.ATTN_ERR_WORKSPACE
+    assert call_wgrad(d, ws_bytes=need - 1) == attn.ATTN_ERR_WORKSPACE
+    for kw in (dict(dtype=attn.ATTN_F32), dict(d=256, stride_n=256, stride_h=128 * 256, stride_b=128 * 256),
+               dict(stride_n=128, stride_h=128 * 128, stride_b=128 * 128)):  # fp32, d > 128, padded rows
+        bad = desc(**kw)
+        assert call_wgrad(bad) == attn.ATTN_ERR_UNSUPPORTED
+        assert L.attn_wgrad_workspace_bytes(ctypes.byref(bad)) == 0
+    assert call_wgrad(desc(batch=0), ptrs=(None,) * 7, ws=None, ws_bytes=0) == attn.ATTN_OK
+    assert call_wgrad(desc(n=0), ptrs=(None,) * 7, ws=None, ws_bytes=0) == attn.ATTN_ERR_INVALID_ARG  # g is written
+
+
 def test_empty_problem_is_ok_without_touching_pointers():
     d = desc(n=0)
     assert call_fwd(d, ptrs=(None,) * 5) == attn.ATTN_OK
