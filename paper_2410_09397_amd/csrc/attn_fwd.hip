@@ -120,10 +120,13 @@ __global__ void __launch_bounds__(kThreads, 2) fwd_kernel(FusedParams p) {
                 for (int i = 0; i < 16; ++i)
                     st[T][i] = (32 * T + 8 * (i >> 2) + (i & 3) > lim) ? -__builtin_inff() : st[T][i];
         }
-        float mx = fmaxf(st[0][0], st[1][0]);
+        // maximum (IEEE-754-2019, v_maximum3_f32) instead of fmaxf: for fmaxf the compiler first
+        // canonicalises every accumulator value (one extra VALU instruction each, for signalling NaNs)
+        float mx = __builtin_elementwise_maximum(st[0][0], st[1][0]);
 #pragma unroll
-        for (int i = 1; i < 16; ++i) mx = fmaxf(mx, fmaxf(st[0][i], st[1][i]));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        for (int i = 1; i < 16; ++i)
+            mx = __builtin_elementwise_maximum(mx, __builtin_elementwise_maximum(st[0][i], st[1][i]));
+        mx = __builtin_elementwise_maximum(mx, __shfl_xor(mx, 32, 64));
         const float m_new = fmaxf(m_run, mx * cs);
         const float m_use = (m_new == -__builtin_inff()) ? 0.f : m_new;  // nothing visible yet
         if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {  // some row's maximum moved: rescale
