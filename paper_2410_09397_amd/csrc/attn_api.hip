@@ -52,7 +52,7 @@ Path pick_path(const attn_desc* d, const attn_blockmask* m) {
 size_t delta_bytes(const attn_desc* d) { return round_up((size_t)d->batch * d->heads * d->n * sizeof(float), 256); }
 
 // Workspace layout of the large-d path.  Backward: [delta][P][dS]; forward: [stat_m][stat_l][P].
-size_t npad_of(const attn_desc* d) { return round_up((size_t)d->n, 128); }
+size_t npad_of(const attn_desc* d) { return round_up((size_t)d->n, 256); }  // the product kernels' row block
 size_t nn_bytes(const attn_desc* d) { return (size_t)d->batch * d->heads * npad_of(d) * npad_of(d) * 2; }
 size_t stat_bytes(const attn_desc* d) {
     return round_up((size_t)d->batch * d->heads * d->n * (npad_of(d) / 64) * sizeof(float), 256);

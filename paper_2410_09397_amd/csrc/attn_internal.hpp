@@ -18,7 +18,7 @@ hipError_t launch_bwd_fused(int d, const FusedParams& p, const int32_t* csr_ptr,
 void launch_delta(const FusedParams& p, int d, hipStream_t stream);
 
 // Arguments of the large-d path (bf16, d in {256, 512}, no block mask).  P and dS are n x n
-// matrices per (batch, head) with row pitch npad = n rounded up to 128, in the workspace.
+// matrices per (batch, head) with row pitch npad = n rounded up to 256, in the workspace.
 struct LargeDParams {
     const __bf16 *Q, *K, *V, *dO;
     __bf16 *Oout, *dQ, *dK, *dV;

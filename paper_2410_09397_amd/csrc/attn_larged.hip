@@ -61,7 +61,20 @@ __global__ void __launch_bounds__(kThreads, 2) ld_scores_kernel(LargeDParams p) 
             kb = tile % nb;
         }
     }
-    if (p.causal && kb > qb) return;  // whole tile above the diagonal: never read downstream
+    if (p.causal && kb > qb) {
+        // Whole tile above the diagonal.  The product kernels work on 256-row blocks of P and dS, so
+        // the tile next to the diagonal tile of an even query block is read there: it is zeroed.
+        // Every other tile above the diagonal is never read.
+        if (MODE != kStats && kb == (qb | 1)) {
+            const u32x4 z = {0, 0, 0, 0};
+            for (int e = threadIdx.x; e < 128 * 16; e += kThreads) {
+                const long off = ((long)bh * p.npad + qb * 128 + e / 16) * p.npad + kb * 128 + (e % 16) * 8;
+                *reinterpret_cast<u32x4*>(p.P + off) = z;
+                if (MODE == kBackward) *reinterpret_cast<u32x4*>(p.dS + off) = z;
+            }
+        }
+        return;
+    }
     const long base = (long)(bh / p.heads) * p.stride_b + (long)(bh % p.heads) * p.stride_h;
     const int k0 = kb * 128, q0 = qb * 128;
     const __bf16* gK = p.K + base;
@@ -219,12 +232,15 @@ struct GemmArgs {
     float alpha;
 };
 
-// k-step of the product kernel: 32 keeps four workgroups per CU resident (32 KB of LDS each)
-constexpr int kGemmBK = 32;
+// Output tile of the product kernel: 256 rows x 128 columns per workgroup, a 128 x 64 block (4 x 2
+// accumulators) per wave: six fragments from LDS feed eight MFMAs, and a k-step of 32 moves 24 KB
+// from global memory for 64 MFMAs.  (With 128 x 128 tiles the copies alone, at the 64 B/clk that
+// the vector memory path delivers per CU, took as long as the MFMAs.)
+constexpr int kGemmBK = 32, kGemmM = 256;
 template <bool A_KMAJOR>
 __global__ void __launch_bounds__(kThreads, 2) ld_gemm_kernel(LargeDParams p, GemmArgs g) {
-    constexpr int BK = kGemmBK;
-    constexpr int kTile = 128 * BK * 2;
+    constexpr int BK = kGemmBK, TM = kGemmM;
+    constexpr int kTileA = TM * BK * 2, kTileB = 128 * BK * 2, kStage = kTileA + kTileB;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, l32 = lane & 31;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, uniform
@@ -233,33 +249,38 @@ __global__ void __launch_bounds__(kThreads, 2) ld_gemm_kernel(LargeDParams p, Ge
     // follow one another on one XCD and share its copy of the A operand
     int bh, mb, n0;
     {
-        const int nt = (p.d + 127) / 128, mbs = p.npad / 128, total = nt * mbs * p.batch * p.heads;
+        const int nt = (p.d + 127) / 128, mbs = p.npad / TM, total = nt * mbs * p.batch * p.heads;
         int t = blockIdx.x;
         if ((total & 7) == 0) t = (t >> 3) + (t & 7) * (total >> 3);
         n0 = (t % nt) * 128;
         mb = (t / nt) % mbs;
         bh = t / (nt * mbs);
     }
-    const int m0 = mb * 128;
+    const int m0 = mb * TM;
     const long base = (long)(bh / p.heads) * p.stride_b + (long)(bh % p.heads) * p.stride_h;
     const __bf16* gA = g.A + (long)bh * p.npad * p.npad;  // npad x npad, zero beyond n
     const __bf16* gB = g.B + base;
     int k_begin = 0, k_end = p.npad;
     if (p.causal) {
         if (A_KMAJOR) k_begin = m0;   // queries at or after this key block
-        else k_end = m0 + 128;        // keys at or before this query block
+        else k_end = m0 + TM;         // keys at or before this query block
     }
 
-    f32x16 c[2][2];
-    zero_acc(c);
+    f32x16 c[4][2];
+#pragma unroll
+    for (int tm = 0; tm < 4; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) c[tm][tn][i] = 0.f;
     // Operand tiles go straight from global memory into the LDS stage that was last read one
     // step ago.  Rows of B past n repeat the last row; they meet columns (rows, if A is read
     // transposed) of A that are zero.
     auto fetch = [&](int k, int stage) {
-        char* at = smem + stage * 2 * kTile;
-        if (A_KMAJOR) load_tile_direct<128, BK>(gA + m0, p.npad, k, p.npad, at, tid);
-        else load_tile_direct<BK, 128>(gA + k, p.npad, m0, p.npad, at, tid);
-        load_tile_direct<128, BK>(gB + n0, p.stride_n, k, p.n, at + kTile, tid);
+        char* at = smem + stage * kStage;
+        if (A_KMAJOR) load_tile_direct<TM, BK>(gA + m0, p.npad, k, p.npad, at, tid);
+        else load_tile_direct<BK, TM>(gA + k, p.npad, m0, p.npad, at, tid);
+        load_tile_direct<128, BK>(gB + n0, p.stride_n, k, p.n, at + kTileA, tid);
     };
     fetch(k_begin, 0);
     wait_direct_loads();
@@ -267,19 +288,19 @@ __global__ void __launch_bounds__(kThreads, 2) ld_gemm_kernel(LargeDParams p, Ge
     int stage = 0;
     for (int k = k_begin; k < k_end; k += BK, stage ^= 1) {
         if (k + BK < k_end) fetch(k + BK, stage ^ 1);
-        const char* at = smem + stage * 2 * kTile;
-        const char* bt = at + kTile;
+        const char* at = smem + stage * kStage;
+        const char* bt = at + kTileA;
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 a[2], b[2];
+            bf16x8 a[4], b[2];
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                a[t] = A_KMAJOR ? load_frag_t<128>(at, 64 * wm + 32 * t, 16 * ks, lane)
-                                : load_frag_perm<BK>(at, 64 * wm + 32 * t, ks, lane);
-                b[t] = load_frag_t<128>(bt, 64 * wn + 32 * t, 16 * ks, lane);
-            }
+            for (int t = 0; t < 4; ++t)
+                a[t] = A_KMAJOR ? load_frag_t<TM>(at, 128 * wm + 32 * t, 16 * ks, lane)
+                                : load_frag_perm<BK>(at, 128 * wm + 32 * t, ks, lane);
 #pragma unroll
-            for (int tm = 0; tm < 2; ++tm)
+            for (int t = 0; t < 2; ++t) b[t] = load_frag_t<128>(bt, 64 * wn + 32 * t, 16 * ks, lane);
+#pragma unroll
+            for (int tm = 0; tm < 4; ++tm)
 #pragma unroll
                 for (int tn = 0; tn < 2; ++tn) c[tm][tn] = mfma32(a[tm], b[tn], c[tm][tn]);
         }
@@ -288,13 +309,13 @@ __global__ void __launch_bounds__(kThreads, 2) ld_gemm_kernel(LargeDParams p, Ge
     }
     // accumulator: lane <-> output column, register <-> output row
 #pragma unroll
-    for (int tm = 0; tm < 2; ++tm)
+    for (int tm = 0; tm < 4; ++tm)
 #pragma unroll
         for (int tn = 0; tn < 2; ++tn) {
             const int col = n0 + 64 * wn + 32 * tn + l32;
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int row = m0 + 64 * wm + 32 * tm + acc_row(i, h);
+                const int row = m0 + 128 * wm + 32 * tm + acc_row(i, h);
                 if (row < p.n && col < p.d) g.C[base + (long)row * p.stride_n + col] = (__bf16)(c[tm][tn][i] * g.alpha);
             }
         }
@@ -304,12 +325,13 @@ static hipError_t set_lds(const void* fn, int bytes) {
     return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
 }
 
+constexpr int kGemmLds = 2 * (kGemmM + 128) * kGemmBK * 2;  // two stages of an A and a B tile
 template <bool A_KMAJOR>
 static void run_gemm(const LargeDParams& p, const __bf16* A, const __bf16* B, __bf16* C, float alpha,
                      hipStream_t stream) {
-    const dim3 grid((unsigned)(((p.d + 127) / 128) * (p.npad / 128) * p.batch * p.heads));
+    const dim3 grid((unsigned)(((p.d + 127) / 128) * (p.npad / kGemmM) * p.batch * p.heads));
     GemmArgs g{A, B, C, alpha};
-    hipLaunchKernelGGL(ld_gemm_kernel<A_KMAJOR>, grid, dim3(kThreads), 2 * 2 * 128 * kGemmBK * 2, stream, p, g);
+    hipLaunchKernelGGL(ld_gemm_kernel<A_KMAJOR>, grid, dim3(kThreads), kGemmLds, stream, p, g);
 }
 
 hipError_t launch_larged(bool backward, const LargeDParams& p, hipStream_t stream) {
@@ -318,8 +340,8 @@ hipError_t launch_larged(bool backward, const LargeDParams& p, hipStream_t strea
         hipError_t e = set_lds(reinterpret_cast<const void*>(ld_scores_kernel<kStats>), 2 * 2 * 128 * 32 * 2);
         if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_scores_kernel<kProbs>), 2 * 2 * 128 * 32 * 2);
         if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_scores_kernel<kBackward>), 2 * 4 * 128 * 32 * 2);
-        if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_gemm_kernel<true>), 2 * 2 * 128 * kGemmBK * 2);
-        if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_gemm_kernel<false>), 2 * 2 * 128 * kGemmBK * 2);
+        if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_gemm_kernel<true>), kGemmLds);
+        if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_gemm_kernel<false>), kGemmLds);
         if (e != hipSuccess) return e;
         configured = true;
     }
