@@ -27,7 +27,7 @@ def cpu_baseline(w, seconds_hint=20.0):
     from oracle import attn_oracle as orc
     from paper_2410_09397_amd import synth
     cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)))
-    n_s = min(w.n, 4096 if w.d <= 128 else 2048)
+    n_s = min(w.n, 8192 if w.d <= 128 else 2048)  # about 10-30 s of host work at the larger shapes
     heads_s = max(1, min(w.batch * w.heads, 2 * cores))
     ws = w.small(name=w.name + "_cpu_sample", batch=1, heads=heads_s, n=n_s)
     inp = synth.make_inputs(ws)

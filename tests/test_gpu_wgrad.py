@@ -73,3 +73,14 @@ def test_wgrad_of_an_empty_sequence_is_zero():
     attn.attn_bwd_wgrad(z, z, z, wts, wts, z, out=g)
     torch.cuda.synchronize()
     assert torch.count_nonzero(g).item() == 0
+
+
+def test_wgrad_at_the_bench_shape_one_head_against_the_oracle():
+    """Workload 3's shape (b2 h32 n8192 d128, causal), as `bench.py --wgrad` launches it; one head is checked
+    against the composed float64 reference (about 10 s of host work)."""
+    w = synth.workload(3)
+    inp = synth.make_wgrad_inputs(w)
+    g = _run_gpu(w, inp, 1.0, True)
+    assert np.isfinite(g).all()
+    b, h = 1, 17
+    assert helpers.rel_err(g[b, h], _composed_reference(inp, b, h, 1.0, True)) <= TOL
