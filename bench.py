@@ -37,8 +37,10 @@ def cpu_baseline(w, seconds_hint=20.0):
     orc.attn_bwd(inp["Q"], inp["K"], inp["V"], O, inp["dO"], LSE, ws.scale, **m)
     dt = time.perf_counter() - t0
     return {"value": ws.bwd_flops() / dt * 1e-12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
-            "sample": "oracle float64 backward on %d heads of the same workload with n cut to %d "
-                      "(d=%d, %s%s), %.1f s" % (heads_s, n_s, ws.d, "causal" if ws.causal else "non-causal",
+            "sample": "oracle float64 backward on %d heads of the same workload %s "
+                      "(d=%d, %s%s), %.1f s" % (heads_s, "at its full n=%d" % n_s if n_s == w.n else
+                                                "with n cut to %d" % n_s, ws.d,
+                                                "causal" if ws.causal else "non-causal",
                                                 ", block-sparse" if ws.sparse else "", dt)}
 
 
