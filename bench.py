@@ -59,6 +59,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", type=int, default=3, help="1..5, index into the metric's configurations")
+    ap.add_argument("--shape", default=None, help="batch,heads,n,d[,causal]: replace the workload's sizes (sweeps); "
+                                                  "the JSON line then names the derived workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--wgrad", action="store_true",
                     help="also time attn_bwd_wgrad (the paper's weight gradient) on the same shape and "
@@ -73,6 +75,8 @@ def main():
     import torch
     from paper_2410_09397_amd import attn, io_bound, synth
     w = synth.workload(args.workload)
+    if args.shape:
+        w = synth.reshaped(w, args.shape)
     dt = {"bf16": torch.bfloat16, "f32": torch.float32}[w.dtype]
     inp = synth.make_inputs(w)
     Q, K, V, dO = (torch.from_numpy(inp[t]).to("cuda").to(dt) for t in ("Q", "K", "V", "dO"))

@@ -71,6 +71,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", required=True, help="workload name as printed in bench.py's config.workload")
     ap.add_argument("--workload-index", type=int, required=True)
+    ap.add_argument("--shape", default=None, help="the --shape string given to bench.py, if any")
     ap.add_argument("--stats", required=True)
     ap.add_argument("--fetch", required=True)
     ap.add_argument("--write", required=True)
@@ -90,16 +91,17 @@ def main():
 
     lines = []
     w = args.workload_index
+    shape = (" --shape %s" % args.shape) if args.shape else ""
     lines.append("# rocprofv3 summary: attention kernels, workload %s\n" % args.workload)
     lines.append("Commands (from the repository root, on one MI355X; `cd /tmp && export TMPDIR=/tmp` first):\n")
     lines.append("```")
-    lines.append("rocprofv3 --kernel-trace --stats -d %s -o w%d --output-format csv -- python bench.py --workload %d "
-                 "--steps 5 --warmup 2 --no-cpu-baseline" % (args.stats, w, w))
+    lines.append("rocprofv3 --kernel-trace --stats -d %s -o w%d --output-format csv -- python bench.py --workload %d%s "
+                 "--steps 5 --warmup 2 --no-cpu-baseline" % (args.stats, w, w, shape))
     for c, d in (("FETCH_SIZE", args.fetch), ("WRITE_SIZE", args.write)):
-        lines.append("rocprofv3 --pmc %s -d %s -o pmc --output-format csv -- python bench.py --workload %d --steps 3 "
-                     "--warmup 1 --no-cpu-baseline --calibrate-copy" % (c, d, w))
-    lines.append("python -m paper_2410_09397_amd.pmc_summary --workload %s --workload-index %d --stats %s --fetch %s "
-                 "--write %s" % (args.workload, w, args.stats, args.fetch, args.write))
+        lines.append("rocprofv3 --pmc %s -d %s -o pmc --output-format csv -- python bench.py --workload %d%s --steps 3 "
+                     "--warmup 1 --no-cpu-baseline --calibrate-copy" % (c, d, w, shape))
+    lines.append("python -m paper_2410_09397_amd.pmc_summary --workload %s --workload-index %d%s --stats %s --fetch %s "
+                 "--write %s" % (args.workload, w, shape, args.stats, args.fetch, args.write))
     lines.append("```\n")
     if args.bench_json and os.path.exists(args.bench_json):
         for l in open(args.bench_json):
@@ -133,6 +135,8 @@ def main():
                      (label, t[0] / 1e6, t[1] / 1e6, t[2] / 1e6, (t[1] + t[2]) / 1e6))
     from paper_2410_09397_amd import io_bound, synth
     wl = synth.workload(w)
+    if args.shape:
+        wl = synth.reshaped(wl, args.shape)
     y = io_bound.yardstick(wl)
     bwd_bytes = tot["bwd"][1] + tot["bwd"][2]
     lines.append("\nPaper's I/O yardstick for the backward (max{compulsory, Theta-term at M = 160 KB}): %.1f MB; "

@@ -77,6 +77,18 @@ def workload(index):
     return WORKLOADS[index - 1]
 
 
+def reshaped(w, shape):
+    """Workload `w` with sizes replaced from a "batch,heads,n,d[,causal]" string (for sweeps over n or d that keep
+    the value distributions and the mask kind of `w`); the name says what was changed."""
+    parts = [int(x) for x in shape.split(",")]
+    if len(parts) not in (4, 5):
+        raise ValueError("shape must be batch,heads,n,d[,causal]")
+    b, h, n, d = parts[:4]
+    causal = bool(parts[4]) if len(parts) == 5 else w.causal
+    return replace(w, name="%s_as_b%d_h%d_n%d_d%d%s" % (w.name.split("_")[0], b, h, n, d, "_causal" if causal else ""),
+                   batch=b, heads=h, n=n, d=d, causal=causal)
+
+
 def _rng(seed, workload_index, tensor_id):
     return np.random.Generator(np.random.Philox(key=[(int(seed) << 8) ^ int(workload_index), int(tensor_id)]))
 
