@@ -61,6 +61,8 @@ def main():
     ap.add_argument("--workload", type=int, default=3, help="1..5, index into the metric's configurations")
     ap.add_argument("--shape", default=None, help="batch,heads,n,d[,causal]: replace the workload's sizes (sweeps); "
                                                   "the JSON line then names the derived workload")
+    ap.add_argument("--extra-frac", type=float, default=None,
+                    help="block-sparse workload only: share of non-diagonal key blocks kept per query-block row")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--wgrad", action="store_true",
                     help="also time attn_bwd_wgrad (the paper's weight gradient) on the same shape and "
@@ -77,6 +79,8 @@ def main():
     w = synth.workload(args.workload)
     if args.shape:
         w = synth.reshaped(w, args.shape)
+    if args.extra_frac is not None:
+        w = synth.with_density(w, args.extra_frac)
     dt = {"bf16": torch.bfloat16, "f32": torch.float32}[w.dtype]
     inp = synth.make_inputs(w)
     Q, K, V, dO = (torch.from_numpy(inp[t]).to("cuda").to(dt) for t in ("Q", "K", "V", "dO"))

@@ -72,6 +72,7 @@ def main():
     ap.add_argument("--workload", required=True, help="workload name as printed in bench.py's config.workload")
     ap.add_argument("--workload-index", type=int, required=True)
     ap.add_argument("--shape", default=None, help="the --shape string given to bench.py, if any")
+    ap.add_argument("--extra-frac", type=float, default=None, help="the --extra-frac given to bench.py, if any")
     ap.add_argument("--stats", required=True)
     ap.add_argument("--fetch", required=True)
     ap.add_argument("--write", required=True)
@@ -92,6 +93,8 @@ def main():
     lines = []
     w = args.workload_index
     shape = (" --shape %s" % args.shape) if args.shape else ""
+    if args.extra_frac is not None:
+        shape += " --extra-frac %g" % args.extra_frac
     lines.append("# rocprofv3 summary: attention kernels, workload %s\n" % args.workload)
     lines.append("Commands (from the repository root, on one MI355X; `cd /tmp && export TMPDIR=/tmp` first):\n")
     lines.append("```")
@@ -137,6 +140,8 @@ def main():
     wl = synth.workload(w)
     if args.shape:
         wl = synth.reshaped(wl, args.shape)
+    if args.extra_frac is not None:
+        wl = synth.with_density(wl, args.extra_frac)
     y = io_bound.yardstick(wl)
     bwd_bytes = tot["bwd"][1] + tot["bwd"][2]
     lines.append("\nPaper's I/O yardstick for the backward (max{compulsory, Theta-term at M = 160 KB}): %.1f MB; "

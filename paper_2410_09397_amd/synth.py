@@ -89,6 +89,13 @@ def reshaped(w, shape):
                    batch=b, heads=h, n=n, d=d, causal=causal)
 
 
+def with_density(w, extra_frac):
+    """Block-sparse workload `w` with another share of non-diagonal key blocks kept per query-block row."""
+    if not w.sparse:
+        raise ValueError("density applies to the block-sparse workload")
+    return replace(w, name="%s_extra%g" % (w.name, extra_frac), extra_frac=float(extra_frac))
+
+
 def _rng(seed, workload_index, tensor_id):
     return np.random.Generator(np.random.Philox(key=[(int(seed) << 8) ^ int(workload_index), int(tensor_id)]))
 
