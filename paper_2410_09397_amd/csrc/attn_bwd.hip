@@ -1,7 +1,8 @@
 // Fused backward kernels for d <= 128 (the regime where a d x d working set fits on chip):
-//   delta   = rowsum(dO o O)                                  (second matrix form of p, App. B.4)
-//   dK, dV  : one workgroup owns a block of 128 keys and streams query tiles
-//   dQ      : one workgroup owns a block of 128 queries and streams key tiles
+//   dQ      : one workgroup owns a block of 128 queries and streams key tiles; its prologue also
+//             forms delta = rowsum(dO o O) (second matrix form of p, App. B.4) for those queries
+//   dK, dV  : one workgroup owns a block of 64 keys and streams query tiles
+//   (delta_kernel, the stand-alone row sum, serves the large-d path)
 // Per tile pair this is the inner body of the paper's large-cache phase-2 algorithm (App. D):
 // q = dO h^T, A = S A_2^T, f = exp(A) / l, p = f o q - diag(v) f, followed by the three
 // products that use f and p.  The resident operand is the owned block, so dK/dV (resp. dQ)

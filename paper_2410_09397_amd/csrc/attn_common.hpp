@@ -122,11 +122,8 @@ struct FragOffsets {
         return *reinterpret_cast<const bf16x8*>(lds + a + row0 * (D * 2));
     }
     // columns 32 mt + l % 32; rows row16 + 8 (t / 4) + 4h + t % 4 with row16 a multiple of 16
-    // `flip` (0 or 8) is XORed into the address: for tiles whose writer swaps the 8-byte halves
-    // of a chunk in some rows
-    __device__ __forceinline__ bf16x8 frag_t(const char* lds, int tile_off_bytes, int mt, int row16,
-                                             int flip = 0) const {
-        const int a = (tile_off_bytes + tr0) ^ (mt << 6) ^ flip;
+    __device__ __forceinline__ bf16x8 frag_t(const char* lds, int tile_off_bytes, int mt, int row16) const {
+        const int a = (tile_off_bytes + tr0) ^ (mt << 6);
         i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 ATTN_LDS*)(lds + a + row16 * (D * 2)));
         i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 ATTN_LDS*)(lds + (a ^ 32) + (row16 + 8) * (D * 2)));
         typedef short i16x8 __attribute__((ext_vector_type(8)));
