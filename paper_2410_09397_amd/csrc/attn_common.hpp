@@ -150,23 +150,23 @@ __device__ __forceinline__ bf16x8 load_frag_perm(const char* tile, int row0, int
 // fetches global chunk p ^ swz(row): the swizzle is applied on the global side.  Rows at or
 // beyond rows_valid re-read the last valid row (finite values that the callers mask out).
 // The copy is complete for the issuing wave after wait_direct_loads().
-template <int D, int ROWS>
+template <int D, int ROWS, int NW = 4>  // NW: waves of the workgroup (all of them take part)
 __device__ __forceinline__ void load_tile_direct(const __bf16* base, long ld, int row_begin, int rows_valid,
                                                  char* tile, int tid) {
     constexpr int kRowsPerInst = 1024 / (D * 2);
-    constexpr int kInst = ROWS / (4 * kRowsPerInst);
-    static_assert(ROWS % (4 * kRowsPerInst) == 0, "tile must split evenly over four waves");
+    constexpr int kInst = ROWS / (NW * kRowsPerInst);
+    static_assert(ROWS % (NW * kRowsPerInst) == 0, "tile must split evenly over the workgroup's waves");
     const int lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
 #pragma unroll
     for (int u = 0; u < kInst; ++u) {
-        const int row = (u * 4 + w) * kRowsPerInst + lane / (D / 8);
+        const int row = (u * NW + w) * kRowsPerInst + lane / (D / 8);
         const int c = (lane % (D / 8)) ^ swz<D>(row);
         const int grow = min(row_begin + row, rows_valid - 1);
         // Issued as inline assembly on purpose: for the builtin the compiler cannot tell which LDS
         // bytes a copy in flight will write and drains all of them (s_waitcnt vmcnt(0)) before the
         // next transposing LDS read, i.e. in the middle of the iteration.  Here the wait is ours:
         // wait_direct_loads() right before the barrier that publishes the stage.
-        const unsigned dst = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(ATTN_LDS char*)(tile + (u * 4 + w) * 1024));
+        const unsigned dst = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(ATTN_LDS char*)(tile + (u * NW + w) * 1024));
         asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
                      :
                      : "s"(dst), "v"(base + (long)grow * ld + c * 8)

@@ -30,44 +30,49 @@ __device__ __forceinline__ void zero_acc(f32x16 (&c)[2][2]) {
 
 enum ScoreMode { kStats = 0, kProbs = 1, kBackward = 2 };
 
-// One workgroup: a 128 (keys) x 128 (queries) tile of S^T (and dP^T), waves in a 2 x 2 grid of
-// 64 x 64 sub-tiles.  Accumulator: lane <-> query, register <-> key.
-template <int MODE>
-__global__ void __launch_bounds__(kThreads, 2) ld_scores_kernel(LargeDParams p) {
-    constexpr int BK = 32;
-    constexpr int kTile = 128 * BK * 2;                       // bytes per operand tile
-    constexpr int kOps = MODE == kBackward ? 4 : 2;           // K, Q (+ V, dO)
+// One workgroup of NW waves: a (32 NW keys) x (128 queries) tile of S^T (and dP^T), waves in an
+// (NW / 2) x 2 grid of 64 x 64 sub-tiles.  Accumulator: lane <-> query, register <-> key.
+// The forward modes run 8 waves on 256 x 128 tiles with three LDS stages (fewer bytes copied per
+// MFMA; 10 % faster there), the backward mode 4 waves on 128 x 128 tiles with two stages and two
+// workgroups per CU (the 8-wave shape measured 15 % slower for it).
+template <int MODE, int NW>
+__global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) ld_scores_kernel(LargeDParams p) {
+    constexpr int BK = 32, kKeys = 32 * NW, kThreadsHere = 64 * NW;
+    constexpr int kTileK = kKeys * BK * 2, kTileQ = 128 * BK * 2;  // bytes per operand tile
+    constexpr int kStage = (MODE == kBackward ? 2 : 1) * (kTileK + kTileQ);  // K, Q (+ V, dO)
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, l32 = lane & 31;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, uniform
     const int wm = w >> 1, wn = w & 1;
-    const int nb = p.npad / 128;
+    const int nbq = p.npad / 128, nbk = p.npad / kKeys;
     // 1-D grid; ids congruent mod 8 share an XCD and its 4 MB L2.  Each XCD gets a contiguous
-    // range of tiles, ordered so that 64 consecutive ones form an 8 x 8 block of (query, key)
-    // tiles: their 32 operand blocks (4 MB at d = 512) are what the L2 can keep.
+    // range of tiles, ordered so that consecutive ones form a block of 8 query tiles x 1024 keys:
+    // their operand blocks (4 MB at d = 512) are what the L2 can keep.
     int bh, kb, qb;
     {
-        const int heads = p.batch * p.heads, total = nb * nb * heads;
+        constexpr int kPerRegionRow = 1024 / kKeys;  // key tiles per region row: 8 or 4
+        const int per_head = nbq * nbk, total = per_head * p.batch * p.heads;
         int t = blockIdx.x;
         if ((total & 7) == 0) t = (t >> 3) + (t & 7) * (total >> 3);
-        bh = t / (nb * nb);
-        const int tile = t % (nb * nb);
-        if ((nb & 7) == 0) {
-            const int region = tile >> 6, in = tile & 63, rpr = nb >> 3;  // regions per row
-            qb = (region / rpr) * 8 + (in >> 3);
-            kb = (region % rpr) * 8 + (in & 7);
+        bh = t / per_head;
+        const int tile = t % per_head;
+        if ((nbq & 7) == 0 && nbk % kPerRegionRow == 0) {
+            const int region = tile / (8 * kPerRegionRow), in = tile % (8 * kPerRegionRow);
+            const int rpr = nbk / kPerRegionRow;  // regions per row
+            qb = (region / rpr) * 8 + in / kPerRegionRow;
+            kb = (region % rpr) * kPerRegionRow + in % kPerRegionRow;
         } else {
-            qb = tile / nb;
-            kb = tile % nb;
+            qb = tile / nbk;
+            kb = tile % nbk;
         }
     }
-    if (p.causal && kb > qb) {
-        // Whole tile above the diagonal.  The product kernels work on 256-row blocks of P and dS, so
-        // the tile next to the diagonal tile of an even query block is read there: it is zeroed.
-        // Every other tile above the diagonal is never read.
-        if (MODE != kStats && kb == (qb | 1)) {
+    if (p.causal && kb * kKeys > qb * 128 + 127) {
+        // Whole tile above the diagonal.  The product kernels work on 256-row blocks of P and dS:
+        // with 128-key tiles the tile next to the diagonal tile of an even query block is read
+        // there and is zeroed here; every other tile above the diagonal is never read.
+        if (kKeys == 128 && MODE != kStats && kb == (qb | 1)) {
             const u32x4 z = {0, 0, 0, 0};
-            for (int e = threadIdx.x; e < 128 * 16; e += kThreads) {
+            for (int e = threadIdx.x; e < 128 * 16; e += kThreadsHere) {
                 const long off = ((long)bh * p.npad + qb * 128 + e / 16) * p.npad + kb * 128 + (e % 16) * 8;
                 *reinterpret_cast<u32x4*>(p.P + off) = z;
                 if (MODE == kBackward) *reinterpret_cast<u32x4*>(p.dS + off) = z;
@@ -76,7 +81,7 @@ __global__ void __launch_bounds__(kThreads, 2) ld_scores_kernel(LargeDParams p) 
         return;
     }
     const long base = (long)(bh / p.heads) * p.stride_b + (long)(bh % p.heads) * p.stride_h;
-    const int k0 = kb * 128, q0 = qb * 128;
+    const int k0 = kb * kKeys, q0 = qb * 128;
     const __bf16* gK = p.K + base;
     const __bf16* gQ = p.Q + base;
     const __bf16* gV = (MODE == kBackward ? p.V : p.K) + base;
@@ -87,32 +92,37 @@ __global__ void __launch_bounds__(kThreads, 2) ld_scores_kernel(LargeDParams p) 
     zero_acc(s);
     if (MODE == kBackward) zero_acc(dp);
 
-    // Operand chunks (128 rows x BK columns each) go straight from global memory into the LDS
+    // Operand chunks (kKeys or 128 rows x BK columns) go straight from global memory into the LDS
     // stage that was last read one chunk ago; rows past n repeat the last row and are masked in
-    // the epilogue.
+    // the epilogue.  Stage layout: [K][Q]([V][dO]).
     auto fetch = [&](int c0, int stage) {
-        char* b = smem + stage * kOps * kTile;
-        load_tile_direct<BK, 128>(gK + c0, ld, k0, p.n, b, tid);
-        load_tile_direct<BK, 128>(gQ + c0, ld, q0, p.n, b + kTile, tid);
+        char* b = smem + stage * kStage;
+        load_tile_direct<BK, kKeys, NW>(gK + c0, ld, k0, p.n, b, tid);
+        load_tile_direct<BK, 128, NW>(gQ + c0, ld, q0, p.n, b + kTileK, tid);
         if (MODE == kBackward) {
-            load_tile_direct<BK, 128>(gV + c0, ld, k0, p.n, b + 2 * kTile, tid);
-            load_tile_direct<BK, 128>(gG + c0, ld, q0, p.n, b + 3 * kTile, tid);
+            load_tile_direct<BK, kKeys, NW>(gV + c0, ld, k0, p.n, b + kTileK + kTileQ, tid);
+            load_tile_direct<BK, 128, NW>(gG + c0, ld, q0, p.n, b + 2 * kTileK + kTileQ, tid);
         }
     };
+    // kStages LDS stages: the copy of chunk kc + kStages - 1 is issued while chunk kc is multiplied
+    // (with one workgroup per CU nothing else hides the copies' latency: three stages there).
+    constexpr int kStages = NW == 8 ? 3 : 2, kAhead = kStages - 1;
+    constexpr int kCopiesPerFetch = (MODE == kBackward ? 2 : 1) * (kTileK + kTileQ) / (1024 * NW);  // per wave
     const int chunks = p.d / BK;
-    fetch(0, 0);
+    for (int c = 0; c < kAhead && c < chunks; ++c) fetch(c * BK, c);
     wait_direct_loads();
     __syncthreads();
     for (int kc = 0; kc < chunks; ++kc) {
-        if (kc + 1 < chunks) fetch((kc + 1) * BK, (kc + 1) & 1);
-        const char* b = smem + (kc & 1) * kOps * kTile;
+        const bool more = kc + kAhead < chunks;
+        if (more) fetch((kc + kAhead) * BK, (kc + kAhead) % kStages);
+        const char* b = smem + (kc % kStages) * kStage;
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
             bf16x8 a[2], q[2];
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
                 a[t] = load_frag<BK>(b, 64 * wm + 32 * t, ks, lane);
-                q[t] = load_frag<BK>(b + kTile, 64 * wn + 32 * t, ks, lane);
+                q[t] = load_frag<BK>(b + kTileK, 64 * wn + 32 * t, ks, lane);
             }
 #pragma unroll
             for (int tm = 0; tm < 2; ++tm)
@@ -121,8 +131,8 @@ __global__ void __launch_bounds__(kThreads, 2) ld_scores_kernel(LargeDParams p) 
             if (MODE == kBackward) {
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
-                    a[t] = load_frag<BK>(b + 2 * kTile, 64 * wm + 32 * t, ks, lane);
-                    q[t] = load_frag<BK>(b + 3 * kTile, 64 * wn + 32 * t, ks, lane);
+                    a[t] = load_frag<BK>(b + kTileK + kTileQ, 64 * wm + 32 * t, ks, lane);
+                    q[t] = load_frag<BK>(b + 2 * kTileK + kTileQ, 64 * wn + 32 * t, ks, lane);
                 }
 #pragma unroll
                 for (int tm = 0; tm < 2; ++tm)
@@ -130,13 +140,15 @@ __global__ void __launch_bounds__(kThreads, 2) ld_scores_kernel(LargeDParams p) 
                     for (int tn = 0; tn < 2; ++tn) dp[tm][tn] = mfma32(a[tm], q[tn], dp[tm][tn]);
             }
         }
-        wait_direct_loads();
+        // chunk kc + 1 must have landed; with three stages the copies just issued may stay in flight
+        if (more && kStages == 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopiesPerFetch) : "memory");
+        else wait_direct_loads();
         __syncthreads();
     }
 
     // epilogue
     const float c = p.scale * kLog2e;
-    const bool need_mask = (p.causal && kb == qb) || (k0 + 128 > p.n);
+    const bool need_mask = (p.causal && k0 + kKeys - 1 > q0) || (k0 + kKeys > p.n);
 #pragma unroll
     for (int tn = 0; tn < 2; ++tn) {
         const int q = q0 + 64 * wn + 32 * tn + l32;
@@ -163,7 +175,7 @@ __global__ void __launch_bounds__(kThreads, 2) ld_scores_kernel(LargeDParams p) 
                 for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(x[tm][i] - m_use);
             sum += __shfl_xor(sum, 32, 64);
             if (q_ok && h == 0) {
-                const long o = ((long)bh * p.n + q) * (2 * nb) + 2 * kb + wm;
+                const long o = ((long)bh * p.n + q) * (2 * nbq) + k0 / 64 + wm;
                 p.stat_m[o] = mx;
                 p.stat_l[o] = sum;
             }
@@ -334,27 +346,31 @@ static void run_gemm(const LargeDParams& p, const __bf16* A, const __bf16* B, __
     hipLaunchKernelGGL(ld_gemm_kernel<A_KMAJOR>, grid, dim3(kThreads), kGemmLds, stream, p, g);
 }
 
+constexpr int kScoreLdsFwd = 3 * (256 + 128) * 32 * 2;      // 8 waves: three stages of a K and a Q chunk
+constexpr int kScoreLdsBwd = 2 * 2 * (128 + 128) * 32 * 2;  // 4 waves: two stages of K, Q, V, dO chunks
 hipError_t launch_larged(bool backward, const LargeDParams& p, hipStream_t stream) {
     static bool configured = false;
     if (!configured) {
-        hipError_t e = set_lds(reinterpret_cast<const void*>(ld_scores_kernel<kStats>), 2 * 2 * 128 * 32 * 2);
-        if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_scores_kernel<kProbs>), 2 * 2 * 128 * 32 * 2);
-        if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_scores_kernel<kBackward>), 2 * 4 * 128 * 32 * 2);
+        hipError_t e = set_lds(reinterpret_cast<const void*>(ld_scores_kernel<kStats, 8>), kScoreLdsFwd);
+        if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_scores_kernel<kProbs, 8>), kScoreLdsFwd);
+        if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_scores_kernel<kBackward, 4>), kScoreLdsBwd);
         if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_gemm_kernel<true>), kGemmLds);
         if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_gemm_kernel<false>), kGemmLds);
         if (e != hipSuccess) return e;
         configured = true;
     }
-    const unsigned nb = (unsigned)(p.npad / 128), bh = (unsigned)(p.batch * p.heads);
-    const dim3 sgrid(nb * nb * bh), block(kThreads);
+    const unsigned bh = (unsigned)(p.batch * p.heads);
+    const unsigned nbq = (unsigned)(p.npad / 128);
+    const dim3 fgrid(nbq * (unsigned)(p.npad / 256) * bh), fblock(512);  // forward modes: 256-key tiles, 8 waves
+    const dim3 bgrid(nbq * nbq * bh), block(kThreads);                   // backward mode: 128-key tiles, 4 waves
     if (!backward) {
-        hipLaunchKernelGGL(ld_scores_kernel<kStats>, sgrid, block, 2 * 2 * 128 * 32 * 2, stream, p);
+        hipLaunchKernelGGL((ld_scores_kernel<kStats, 8>), fgrid, fblock, kScoreLdsFwd, stream, p);
         const long rows = (long)bh * p.n;
         hipLaunchKernelGGL(ld_lse_combine_kernel, dim3((unsigned)((rows + kThreads - 1) / kThreads)), block, 0, stream, p);
-        hipLaunchKernelGGL(ld_scores_kernel<kProbs>, sgrid, block, 2 * 2 * 128 * 32 * 2, stream, p);
+        hipLaunchKernelGGL((ld_scores_kernel<kProbs, 8>), fgrid, fblock, kScoreLdsFwd, stream, p);
         run_gemm<false>(p, p.P, p.V, p.Oout, 1.f, stream);
     } else {
-        hipLaunchKernelGGL(ld_scores_kernel<kBackward>, sgrid, block, 2 * 4 * 128 * 32 * 2, stream, p);
+        hipLaunchKernelGGL((ld_scores_kernel<kBackward, 4>), bgrid, block, kScoreLdsBwd, stream, p);
         run_gemm<true>(p, p.P, p.dO, p.dV, 1.f, stream);
         run_gemm<true>(p, p.dS, p.Q, p.dK, p.scale, stream);
         run_gemm<false>(p, p.dS, p.K, p.dQ, p.scale, stream);
