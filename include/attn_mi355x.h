@@ -56,7 +56,7 @@ typedef struct {
     float scale;    /* multiplies Q K^T; callers usually pass 1/sqrt(d) */
     int32_t causal; /* 0 or 1: key j visible to query i iff j <= i */
     int32_t dtype;  /* attn_dtype of Q, K, V, O, dO, dQ, dK, dV */
-    int64_t stride_b, stride_h, stride_n; /* in elements; the d axis has stride 1 */
+    int64_t stride_b, stride_h, stride_n; /* in elements; the d axis has stride 1; stride_n < 2^22 */
 } attn_desc;
 
 /*

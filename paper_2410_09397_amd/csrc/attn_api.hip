@@ -30,6 +30,8 @@ attn_status check_desc(const attn_desc* d) {
     if (d->stride_n < d->d || d->stride_h < 0 || d->stride_b < 0) return ATTN_ERR_INVALID_ARG;
     if (d->dtype == ATTN_BF16 && (d->stride_n % 8 || d->stride_h % 8 || d->stride_b % 8))
         return ATTN_ERR_INVALID_ARG;
+    // the tile copies address a tile's rows with 32-bit byte offsets from its first row
+    if (d->stride_n >= (int64_t)1 << 22) return ATTN_ERR_UNSUPPORTED;
     return ATTN_OK;
 }
 

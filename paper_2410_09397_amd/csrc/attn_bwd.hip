@@ -113,10 +113,12 @@ __global__ void __launch_bounds__(kThreads, 2) bwd_dkdv_kernel(FusedParams p) {
     // the next iteration, so nothing waits on the copies in flight behind them.
     float lse_raw = 0.f, delta_raw = 0.f;
     bool row_ok = false;
-    auto fetch = [&](int i0, int stage) {
-        char* s = smem + stage * kStageBytes;
-        load_tile_direct<D, BR>(p.Q + base, ld, i0, p.n, s, tid);
-        load_tile_direct<D, BR>(p.dO + base, ld, i0, p.n, s + kTileBytes, tid);
+    TileLoader<D, BR> loader;
+    loader.init(tid, ld);
+    auto fetch = [&](int i0, int stage_off) {
+        char* s = smem + stage_off;
+        loader.load(p.Q + base, ld, i0, p.n, s, tid);
+        loader.load(p.dO + base, ld, i0, p.n, s + kTileBytes, tid);
         const int q = i0 + 32 * wx + l32;
         row_ok = q < p.n;
         lse_raw = lse_g[min(q, p.n - 1)];
@@ -143,16 +145,35 @@ __global__ void __launch_bounds__(kThreads, 2) bwd_dkdv_kernel(FusedParams p) {
     // hit every bank twice.  The transposed reads apply the same swap per lane.
     const int p_wr = tile_off<BC>(32 * wx + l32, 4 * wk) + 8 * (h ^ (l32 & 1));
     fp.tr0 ^= (((lane & 15) >> 2) & 1) << 3;
+    // Address registers of everything this wave reads from or writes to LDS, relative to the
+    // stage (all wave-dependent tile choices folded in): a fetch is then a register plus an
+    // immediate, with no vector arithmetic in the loop.
+    //   q_rm[ks]     Q rows 32 wx + l32 (phase 1; the dO tile is kTileBytes further)
+    //   a_tr[m][.]   phase-2 A operand: dO^T (wx = 0) or Q^T (wx = 1), columns 32 (MH wk + m) ..
+    //   b_tr[kt][.]  phase-2 B operand: P (wx = 0) or dS (wx = 1), keys 32 kt ..
+    //   p_slot[g]    this lane's slot in the P tile (the dS tile is kPBytes further)
+    int q_rm[KS], a_tr[MT / 2][2], b_tr[2][2], p_slot[4];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) q_rm[ks] = fo.rm(ks) + 32 * wx * (D * 2);
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+#pragma unroll
+        for (int m = 0; m < MT / 2; ++m) a_tr[m][half] = fo.tr((MT / 2) * wk + m, half) + (wx == 0 ? kTileBytes : 0);
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt) b_tr[kt][half] = fp.tr(kt, half) + (wx == 0 ? kPOff : kDsOff);
+    }
+#pragma unroll
+    for (int g = 0; g < 4; ++g) p_slot[g] = kPOff + (p_wr ^ (g << 4));
     // One streamed query tile (two barriers).  `masked` selects the copy of phase 1 that applies
     // the causal bound.
-    auto tile = [&](int it, int i0, bool skip, auto masked) {
+    auto tile = [&](auto stage_off, int it, int i0, bool skip, auto masked) {
         const float lse_cur = row_ok ? lse_raw * kLog2e : __builtin_inff();
         const float delta_cur = row_ok ? delta_raw : 0.f;
+        const int q_off = stage_off;  // Q tile; the dO tile follows it
         if (it + 1 < n_it) {
             i0_next = tile_start(it + 1);
-            fetch(i0_next, (it + 1) & 1);  // that stage was last read before barrier B
+            fetch(i0_next, kStageBytes - q_off);  // that stage was last read before barrier B
         }
-        const int q_off = (it & 1) * kStageBytes;  // Q tile; the dO tile follows it
         __builtin_amdgcn_s_setprio(kPrioPhase1);
         if (!skip) {
             // ---- phase 1: S^T, dP^T for (key half wk) x (query half wx); the resident K / V
@@ -160,16 +181,16 @@ __global__ void __launch_bounds__(kThreads, 2) bwd_dkdv_kernel(FusedParams p) {
             f32x16 s, dp;
 #pragma unroll
             for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
-            const int qrow_off = q_off + 32 * wx * (D * 2);
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {  // two independent accumulation chains, interleaved
-                s = mfma32(kf[ks], fo.frag(smem, qrow_off, 0, ks), s);
-                dp = mfma32(vf[ks], fo.frag(smem, qrow_off + kTileBytes, 0, ks), dp);
+                s = mfma32(kf[ks], FragOffsets<D>::read(smem, q_rm[ks], q_off), s);
+                dp = mfma32(vf[ks], FragOffsets<D>::read(smem, q_rm[ks], q_off + kTileBytes), dp);
             }
             __builtin_amdgcn_sched_barrier(0);
             __builtin_amdgcn_s_setprio(kPrioSoftmax);
             // key j0 + 32 wk + 8g + 4h + r is visible to this lane's query iff 8g + r <= lim
-            const int lim = i0 + 32 * wx + l32 - j0 - 32 * wk - 4 * h;
+            // (the masked body also serves unpaired tiles of unmasked runs)
+            const int lim = p.causal ? i0 + 32 * wx + l32 - j0 - 32 * wk - 4 * h : 0x7fffffff;
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 float pv[4], dsv[4];
@@ -182,14 +203,13 @@ __global__ void __launch_bounds__(kThreads, 2) bwd_dkdv_kernel(FusedParams p) {
                     dsv[r] = v * (dp[i] - delta_cur);
                 }
                 // [query][key] tiles: four consecutive keys of this lane's query
-                const int off = p_wr ^ (g << 4);
                 u32x2 a, b;
                 a[0] = pack_bf16(pv[0], pv[1]);
                 a[1] = pack_bf16(pv[2], pv[3]);
                 b[0] = pack_bf16(dsv[0], dsv[1]);
                 b[1] = pack_bf16(dsv[2], dsv[3]);
-                *reinterpret_cast<u32x2*>(smem + kPOff + off) = a;
-                *reinterpret_cast<u32x2*>(smem + kDsOff + off) = b;
+                *reinterpret_cast<u32x2*>(smem + p_slot[g]) = a;
+                *reinterpret_cast<u32x2*>(smem + p_slot[g] + kPBytes) = b;
             }
         }
         lds_barrier();  // P, dS visible; the tile copies for the next iteration stay in flight
@@ -197,14 +217,14 @@ __global__ void __launch_bounds__(kThreads, 2) bwd_dkdv_kernel(FusedParams p) {
         if (!skip) {
             // ---- phase 2: dV^T = dO^T P (wx = 0) or dK^T = Q^T dS (wx = 1) for d half wk over the
             // 64 queries and 64 keys
-            const int a_off = wx == 0 ? q_off + kTileBytes : q_off;
-            const int b_off = wx == 0 ? kPOff : kDsOff;
             bf16x8 at[2][MH], bt[2][2];
             auto request = [&](int ks) {
 #pragma unroll
-                for (int m = 0; m < MH; ++m) at[ks & 1][m] = fo.frag_t(smem, a_off, MH * wk + m, 16 * ks);
+                for (int m = 0; m < MH; ++m)
+                    at[ks & 1][m] = FragOffsets<D>::read_t(smem, a_tr[m][0], a_tr[m][1], 16 * ks, q_off);
 #pragma unroll
-                for (int kt = 0; kt < 2; ++kt) bt[ks & 1][kt] = fp.frag_t(smem, b_off, kt, 16 * ks);
+                for (int kt = 0; kt < 2; ++kt)
+                    bt[ks & 1][kt] = FragOffsets<BC>::read_t(smem, b_tr[kt][0], b_tr[kt][1], 16 * ks);
             };
             request(0);
 #pragma unroll
@@ -220,14 +240,21 @@ __global__ void __launch_bounds__(kThreads, 2) bwd_dkdv_kernel(FusedParams p) {
         __syncthreads();
     };
     // Query tiles come in ascending order: under the causal rule the ones that straddle the
-    // diagonal (or lie wholly above it) are the first, then everything is visible.
+    // diagonal (or lie wholly above it) are the first, then everything is visible.  The visible
+    // ones go two at a time through a body whose LDS stage offsets are compile-time constants;
+    // the masked body (run-time stage) also takes the tile that makes the pairs start at an even
+    // index and the one left over at the end.
     int it = 0;
     for (; it < n_it; ++it) {
         const int i0 = i0_next;
-        if (!(p.causal && i0 < j0 + BC - 1)) break;
-        tile(it, i0, i0 + BR - 1 < j0, std::true_type{});
+        if (!(p.causal && i0 < j0 + BC - 1) && !(it & 1)) break;
+        tile((it & 1) * kStageBytes, it, i0, i0 + BR - 1 < j0, std::true_type{});
     }
-    for (; it < n_it; ++it) tile(it, i0_next, false, std::false_type{});
+    for (; it + 2 <= n_it; it += 2) {
+        tile(std::integral_constant<int, 0>{}, it, i0_next, false, std::false_type{});
+        tile(std::integral_constant<int, kStageBytes>{}, it + 1, i0_next, false, std::false_type{});
+    }
+    for (; it < n_it; ++it) tile((it & 1) * kStageBytes, it, i0_next, false, std::true_type{});
 
     const float f = wx == 0 ? 1.f : p.scale;
 #pragma unroll
@@ -338,14 +365,18 @@ __global__ void __launch_bounds__(kThreads, QT == 1 ? 2 : 1) bwd_dq_kernel(Fused
         settle(lse2[t]);
         settle(dl[t]);
     }
-    FragOffsets<D> fo;
-    fo.init(lane);
+    FragOffsets<D> lane_offsets;
+    lane_offsets.init(lane);
+    FragAddrs<D> fo;
+    fo.init(lane_offsets);
     // K and V tiles go straight from global memory into the LDS stage that was last read one
     // iteration ago; rows past n repeat the last row and are masked below.
+    TileLoader<D, BC> loader;
+    loader.init(tid, ld);
     auto fetch = [&](int j0, int stage) {
         char* s = smem + stage * kStageBytes;
-        load_tile_direct<D, BC>(p.K + base, ld, j0, p.n, s, tid);
-        load_tile_direct<D, BC>(p.V + base, ld, j0, p.n, s + kTileBytes, tid);
+        loader.load(p.K + base, ld, j0, p.n, s, tid);
+        loader.load(p.V + base, ld, j0, p.n, s + kTileBytes, tid);
     };
     int j0_next = n_it > 0 ? tile_start(0) : 0;
     if (n_it > 0) fetch(j0_next, 0);
@@ -358,8 +389,8 @@ __global__ void __launch_bounds__(kThreads, QT == 1 ? 2 : 1) bwd_dq_kernel(Fused
     // Wave priorities per phase (see the forward kernel): score MFMAs, then the dQ MFMAs, the
     // exponentials last.
     constexpr int kPrioScores = 2, kPrioSoftmax = 0, kPrioDq = 1;
-    auto tile = [&](int it, int j0, auto masked) {
-        const int k_off = (it & 1) * kStageBytes;  // K tile; the V tile follows it
+    auto tile = [&](auto stage_off, int j0, auto masked) {
+        const int k_off = stage_off;  // K tile; the V tile follows it
         // the two 32-key halves one after the other: half the score registers live at a time
 #pragma unroll
         for (int T = 0; T < 2; ++T) {
@@ -413,18 +444,26 @@ __global__ void __launch_bounds__(kThreads, QT == 1 ? 2 : 1) bwd_dq_kernel(Fused
         }
     };
     // Tiles come in ascending key order, so those that need the bound (they straddle the
-    // diagonal or the end of the sequence) are the last ones: a mask-free loop first, then a
-    // masked loop.  Waves may switch loops at different tiles; both loops run the same barriers.
+    // diagonal or the end of the sequence) are the last ones.  Mask-free tiles go two at a time
+    // through a body whose LDS stage offsets are compile-time constants (fragment addresses are
+    // then a precomputed register plus an immediate); the rest takes the masked body with a
+    // run-time stage.  Waves may leave the first loop at different tiles; both loops run the same
+    // fetches and barriers.
     auto needs_mask = [&](int j0) { return (p.causal && (j0 + BC - 1 > w0)) || (j0 + BC > p.n); };
     int it = 0;
-    for (; it < n_it; ++it) {
-        const int j0 = j0_next;
-        if (needs_mask(j0)) break;
-        if (it + 1 < n_it) {
-            j0_next = tile_start(it + 1);
-            fetch(j0_next, (it + 1) & 1);
+    for (; it + 2 <= n_it; it += 2) {
+        const int ja = j0_next, jb = tile_start(it + 1);
+        if (needs_mask(ja) || needs_mask(jb)) break;
+        j0_next = jb;
+        fetch(jb, 1);
+        tile(std::integral_constant<int, 0>{}, ja, std::false_type{});
+        wait_direct_loads();
+        __syncthreads();
+        if (it + 2 < n_it) {
+            j0_next = tile_start(it + 2);
+            fetch(j0_next, 0);
         }
-        tile(it, j0, std::false_type{});
+        tile(std::integral_constant<int, kStageBytes>{}, jb, std::false_type{});
         wait_direct_loads();
         __syncthreads();
     }
@@ -435,7 +474,7 @@ __global__ void __launch_bounds__(kThreads, QT == 1 ? 2 : 1) bwd_dq_kernel(Fused
             fetch(j0_next, (it + 1) & 1);
         }
         // causal: this wave's last query precedes the tile's first key -> nothing visible
-        if (!(p.causal && (w0 + 32 * QT - 1 < j0))) tile(it, j0, std::true_type{});
+        if (!(p.causal && (w0 + 32 * QT - 1 < j0))) tile((it & 1) * kStageBytes, j0, std::true_type{});
         wait_direct_loads();
         __syncthreads();
     }

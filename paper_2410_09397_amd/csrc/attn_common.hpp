@@ -124,11 +124,47 @@ struct FragOffsets {
     // columns 32 mt + l % 32; rows row16 + 8 (t / 4) + 4h + t % 4 with row16 a multiple of 16
     __device__ __forceinline__ bf16x8 frag_t(const char* lds, int tile_off_bytes, int mt, int row16) const {
         const int a = (tile_off_bytes + tr0) ^ (mt << 6);
-        i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 ATTN_LDS*)(lds + a + row16 * (D * 2)));
-        i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 ATTN_LDS*)(lds + (a ^ 32) + (row16 + 8) * (D * 2)));
+        return read_t(lds, a, a ^ 32, row16);
+    }
+    // Per-fetch address registers for loops whose tile offsets are compile-time constants: with
+    //   rm(ks)       = rm0 ^ (ks << 5)              (+ any multiple of 256)
+    //   tr(mt, half) = tr0 ^ (mt << 6) ^ (half << 5)
+    // kept in registers, a fetch is a register plus an immediate and needs no vector arithmetic.
+    __device__ __forceinline__ int rm(int ks) const { return rm0 ^ (ks << 5); }
+    __device__ __forceinline__ int tr(int mt, int half) const { return tr0 ^ (mt << 6) ^ (half << 5); }
+    static __device__ __forceinline__ bf16x8 read(const char* lds, int rm_ks, int imm) {
+        return *reinterpret_cast<const bf16x8*>(lds + rm_ks + imm);
+    }
+    // imm: tile offset + row16 * row bytes
+    static __device__ __forceinline__ bf16x8 read_t(const char* lds, int tr_lo, int tr_hi, int row16, int imm = 0) {
+        i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 ATTN_LDS*)(lds + tr_lo + (imm + row16 * (D * 2))));
+        i16x4 hi =
+            __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 ATTN_LDS*)(lds + tr_hi + (imm + (row16 + 8) * (D * 2))));
         typedef short i16x8 __attribute__((ext_vector_type(8)));
         i16x8 r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
         return __builtin_bit_cast(bf16x8, r);
+    }
+};
+
+// The address registers of all fragments of a [rows x D] tile (static indices only).
+template <int D>
+struct FragAddrs {
+    int rmk[D / 16];
+    int trk[D / 32][2];
+    __device__ __forceinline__ void init(const FragOffsets<D>& fo) {
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) rmk[ks] = fo.rm(ks);
+#pragma unroll
+        for (int mt = 0; mt < D / 32; ++mt) {
+            trk[mt][0] = fo.tr(mt, 0);
+            trk[mt][1] = fo.tr(mt, 1);
+        }
+    }
+    __device__ __forceinline__ bf16x8 frag(const char* lds, int tile_off_bytes, int row0, int ks) const {
+        return FragOffsets<D>::read(lds, rmk[ks], tile_off_bytes + row0 * (D * 2));
+    }
+    __device__ __forceinline__ bf16x8 frag_t(const char* lds, int tile_off_bytes, int mt, int row16) const {
+        return FragOffsets<D>::read_t(lds, trk[mt][0], trk[mt][1], row16, tile_off_bytes);
     }
 };
 
@@ -174,6 +210,53 @@ __device__ __forceinline__ void load_tile_direct(const __bf16* base, long ld, in
     }
 }
 __device__ __forceinline__ void wait_direct_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// The same copy for the tiles of a streaming loop, with everything that does not change from
+// tile to tile taken out of the loop: each lane keeps the byte offset of its 16 bytes relative to
+// the tile's first row (one register per copy instruction), the tile's first row is a scalar
+// base address, and a copy is one instruction with no vector arithmetic in front of it.
+// (Address arithmetic per copy - a 64-bit multiply-add, a clamp, the swizzle - is as expensive
+// on the vector unit as the MFMA it feeds.)  Tiles that reach past rows_valid take the
+// clamping path of load_tile_direct.  Offsets are 32-bit: ROWS * ld * 2 must stay below 2^32.
+template <int D, int ROWS, int NW = 4>
+struct TileLoader {
+    static constexpr int kRowsPerInst = 1024 / (D * 2);
+    static constexpr int kInst = ROWS / (NW * kRowsPerInst);
+    static_assert(ROWS % (NW * kRowsPerInst) == 0, "tile must split evenly over the workgroup's waves");
+    unsigned voff[kInst];
+    unsigned lds0;  // byte offset of this wave's first 1 KB piece inside a tile
+    __device__ __forceinline__ void init(int tid, long ld) {
+        const int lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+#pragma unroll
+        for (int u = 0; u < kInst; ++u) {
+            const int row = (u * NW + w) * kRowsPerInst + lane / (D / 8);
+            const int c = (lane % (D / 8)) ^ swz<D>(row);
+            voff[u] = (unsigned)row * (unsigned)ld * 2u + (unsigned)c * 16u;
+        }
+        lds0 = (unsigned)w * 1024u;
+    }
+    // first_row: address of the tile's first row (uniform); all ROWS rows must exist
+    __device__ __forceinline__ void load(const __bf16* first_row, char* tile) const {
+        const unsigned t0 =
+            __builtin_amdgcn_readfirstlane((unsigned)(size_t)(ATTN_LDS char*)tile) + lds0;
+#pragma unroll
+        for (int u = 0; u < kInst; ++u) {
+            const unsigned dst = t0 + u * NW * 1024;
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(dst), "v"(voff[u]), "s"(first_row)
+                         : "memory");
+        }
+    }
+    // any tile: clamps rows at rows_valid - 1 when the tile reaches past the end
+    __device__ __forceinline__ void load(const __bf16* base, long ld, int row_begin, int rows_valid, char* tile,
+                                         int tid) const {
+        if (row_begin + ROWS <= rows_valid)
+            load(base + (long)row_begin * ld, tile);
+        else
+            load_tile_direct<D, ROWS, NW>(base, ld, row_begin, rows_valid, tile, tid);
+    }
+};
 
 // Marks a register value as used here.  Ordinary global loads issued before the streaming loop
 // must be complete before it starts: otherwise the compiler's own wait for them lands inside the

@@ -77,14 +77,18 @@ __global__ void __launch_bounds__(kThreads, 2) fwd_kernel(FusedParams p) {
     }
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) settle(qf[ks]);
-    FragOffsets<D> fo;
-    fo.init(lane);
+    FragOffsets<D> lane_offsets;
+    lane_offsets.init(lane);
+    FragAddrs<D> fo;
+    fo.init(lane_offsets);
     // K and V tiles go straight from global memory into the LDS stage that was last read one
     // iteration ago; rows past n repeat the last row and are masked below.
+    TileLoader<D, BC> loader;
+    loader.init(tid, ld);
     auto fetch = [&](int j0, int stage) {
         char* s = smem + stage * kStageBytes;
-        load_tile_direct<D, BC>(p.K + base, ld, j0, p.n, s, tid);
-        load_tile_direct<D, BC>(p.V + base, ld, j0, p.n, s + kTileBytes, tid);
+        loader.load(p.K + base, ld, j0, p.n, s, tid);
+        loader.load(p.V + base, ld, j0, p.n, s + kTileBytes, tid);
     };
     int j0_next = n_it > 0 ? tile_start(0) : 0;
     if (n_it > 0) fetch(j0_next, 0);
@@ -97,8 +101,8 @@ __global__ void __launch_bounds__(kThreads, 2) fwd_kernel(FusedParams p) {
     // Ranking the phases - score MFMAs first, then the PV MFMAs, the exponentials last - lets one
     // wave run ahead while the other fills the gaps (measured: 5-7 % faster at d = 128).
     constexpr int kPrioScores = 2, kPrioSoftmax = 0, kPrioPV = 1;
-    auto tile = [&](int it, int j0, auto masked) {
-        const int k_off = (it & 1) * kStageBytes;  // K tile; the V tile follows it
+    auto tile = [&](auto stage_off, int j0, auto masked) {
+        const int k_off = stage_off;  // K tile; the V tile follows it
         __builtin_amdgcn_s_setprio(kPrioScores);
         f32x16 st[2];
 #pragma unroll
@@ -171,18 +175,26 @@ __global__ void __launch_bounds__(kThreads, 2) fwd_kernel(FusedParams p) {
         }
     };
     // Tiles come in ascending key order, so those that need the bound (they straddle the
-    // diagonal or the end of the sequence) are the last ones: a mask-free loop first, then a
-    // masked loop.  Waves may switch loops at different tiles; both loops run the same barriers.
+    // diagonal or the end of the sequence) are the last ones.  Mask-free tiles go two at a time
+    // through a body whose LDS stage offsets are compile-time constants (fragment addresses are
+    // then a precomputed register plus an immediate: no vector arithmetic per fetch); the rest
+    // takes the masked body with a run-time stage.  Waves may leave the first loop at different
+    // tiles; both loops run the same fetches and barriers.
     auto needs_mask = [&](int j0) { return (p.causal && (j0 + BC - 1 > i0 + 32 * w)) || (j0 + BC > p.n); };
     int it = 0;
-    for (; it < n_it; ++it) {
-        const int j0 = j0_next;
-        if (needs_mask(j0)) break;
-        if (it + 1 < n_it) {
-            j0_next = tile_start(it + 1);
-            fetch(j0_next, (it + 1) & 1);
+    for (; it + 2 <= n_it; it += 2) {
+        const int ja = j0_next, jb = tile_start(it + 1);
+        if (needs_mask(ja) || needs_mask(jb)) break;
+        j0_next = jb;
+        fetch(jb, 1);
+        tile(std::integral_constant<int, 0>{}, ja, std::false_type{});
+        wait_direct_loads();
+        __syncthreads();
+        if (it + 2 < n_it) {
+            j0_next = tile_start(it + 2);
+            fetch(j0_next, 0);
         }
-        tile(it, j0, std::false_type{});
+        tile(std::integral_constant<int, kStageBytes>{}, jb, std::false_type{});
         wait_direct_loads();
         __syncthreads();
     }
@@ -193,7 +205,7 @@ __global__ void __launch_bounds__(kThreads, 2) fwd_kernel(FusedParams p) {
             fetch(j0_next, (it + 1) & 1);
         }
         // causal: this wave's last query precedes the tile's first key -> nothing visible
-        if (!(p.causal && (i0 + 32 * w + 31 < j0))) tile(it, j0, std::true_type{});
+        if (!(p.causal && (i0 + 32 * w + 31 < j0))) tile((it & 1) * kStageBytes, j0, std::true_type{});
         wait_direct_loads();
         __syncthreads();
     }
