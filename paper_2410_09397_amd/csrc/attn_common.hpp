@@ -248,6 +248,12 @@ struct TileLoader {
                          : "memory");
         }
     }
+    // copy instruction u of load() on its own, for callers that spread the copies over their MFMAs
+    __device__ __forceinline__ void load_one(int u, const __bf16* first_row, char* tile) const {
+        const unsigned dst =
+            __builtin_amdgcn_readfirstlane((unsigned)(size_t)(ATTN_LDS char*)tile) + lds0 + u * NW * 1024;
+        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(dst), "v"(voff[u]), "s"(first_row));
+    }
     // any tile: clamps rows at rows_valid - 1 when the tile reaches past the end
     __device__ __forceinline__ void load(const __bf16* base, long ld, int row_begin, int rows_valid, char* tile,
                                          int tid) const {

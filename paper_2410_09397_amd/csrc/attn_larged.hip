@@ -10,6 +10,8 @@
 //                   k-loop over n (phase 4 written for dQ/dK/dV instead of A_1^T p A_2)
 // The forward uses the same kernels: partial row statistics of S per 64-key chunk, a combine
 // step for LSE, P = exp(S - LSE) written to HBM, and O = P V.
+#include <type_traits>
+
 #include "attn_common.hpp"
 #include "attn_internal.hpp"
 
@@ -94,16 +96,28 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) ld_scores_kernel(Lar
 
     // Operand chunks (kKeys or 128 rows x BK columns) go straight from global memory into the LDS
     // stage that was last read one chunk ago; rows past n repeat the last row and are masked in
-    // the epilogue.  Stage layout: [K][Q]([V][dO]).
+    // the epilogue.  Stage layout: [K][Q]([V][dO]).  Lane offsets of the copies and of the
+    // fragment reads are computed once: the loop itself has no address arithmetic.
+    TileLoader<BK, kKeys, NW> copy_k;
+    TileLoader<BK, 128, NW> copy_q;
+    copy_k.init(tid, ld);
+    copy_q.init(tid, ld);
     auto fetch = [&](int c0, int stage) {
         char* b = smem + stage * kStage;
-        load_tile_direct<BK, kKeys, NW>(gK + c0, ld, k0, p.n, b, tid);
-        load_tile_direct<BK, 128, NW>(gQ + c0, ld, q0, p.n, b + kTileK, tid);
+        copy_k.load(gK + c0, ld, k0, p.n, b, tid);
+        copy_q.load(gQ + c0, ld, q0, p.n, b + kTileK, tid);
         if (MODE == kBackward) {
-            load_tile_direct<BK, kKeys, NW>(gV + c0, ld, k0, p.n, b + kTileK + kTileQ, tid);
-            load_tile_direct<BK, 128, NW>(gG + c0, ld, q0, p.n, b + 2 * kTileK + kTileQ, tid);
+            copy_k.load(gV + c0, ld, k0, p.n, b + kTileK + kTileQ, tid);
+            copy_q.load(gG + c0, ld, q0, p.n, b + 2 * kTileK + kTileQ, tid);
         }
     };
+    // fragment of rows row0 + 32 t + l32, k-step ks: register + 32 t row pitches + stage offset
+    int rk[BK / 16], rq[BK / 16];
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+        rk[ks] = tile_off<BK>(64 * wm + l32, 2 * ks + h);
+        rq[ks] = tile_off<BK>(64 * wn + l32, 2 * ks + h) + kTileK;
+    }
     // kStages LDS stages: the copy of chunk kc + kStages - 1 is issued while chunk kc is multiplied
     // (with one workgroup per CU nothing else hides the copies' latency: three stages there).
     constexpr int kStages = NW == 8 ? 3 : 2, kAhead = kStages - 1;
@@ -112,17 +126,17 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) ld_scores_kernel(Lar
     for (int c = 0; c < kAhead && c < chunks; ++c) fetch(c * BK, c);
     wait_direct_loads();
     __syncthreads();
-    for (int kc = 0; kc < chunks; ++kc) {
+    auto chunk = [&](int kc, auto stage_off) {
+        const int so = stage_off;  // a compile-time constant in the unrolled two-stage loop
         const bool more = kc + kAhead < chunks;
         if (more) fetch((kc + kAhead) * BK, (kc + kAhead) % kStages);
-        const char* b = smem + (kc % kStages) * kStage;
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
             bf16x8 a[2], q[2];
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
-                a[t] = load_frag<BK>(b, 64 * wm + 32 * t, ks, lane);
-                q[t] = load_frag<BK>(b + kTileK, 64 * wn + 32 * t, ks, lane);
+                a[t] = FragOffsets<BK>::read(smem, rk[ks], so + 32 * t * (BK * 2));
+                q[t] = FragOffsets<BK>::read(smem, rq[ks], so + 32 * t * (BK * 2));
             }
 #pragma unroll
             for (int tm = 0; tm < 2; ++tm)
@@ -131,8 +145,8 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) ld_scores_kernel(Lar
             if (MODE == kBackward) {
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
-                    a[t] = load_frag<BK>(b + kTileK + kTileQ, 64 * wm + 32 * t, ks, lane);
-                    q[t] = load_frag<BK>(b + 2 * kTileK + kTileQ, 64 * wn + 32 * t, ks, lane);
+                    a[t] = FragOffsets<BK>::read(smem, rk[ks], so + kTileK + kTileQ + 32 * t * (BK * 2));
+                    q[t] = FragOffsets<BK>::read(smem, rq[ks], so + kTileK + kTileQ + 32 * t * (BK * 2));
                 }
 #pragma unroll
                 for (int tm = 0; tm < 2; ++tm)
@@ -144,6 +158,16 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) ld_scores_kernel(Lar
         if (more && kStages == 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopiesPerFetch) : "memory");
         else wait_direct_loads();
         __syncthreads();
+    };
+    if constexpr (kStages == 2) {
+        int kc = 0;
+        for (; kc + 2 <= chunks; kc += 2) {
+            chunk(kc, std::integral_constant<int, 0>{});
+            chunk(kc + 1, std::integral_constant<int, kStage>{});
+        }
+        if (kc < chunks) chunk(kc, std::integral_constant<int, 0>{});
+    } else {
+        for (int kc = 0; kc < chunks; ++kc) chunk(kc, (kc % kStages) * kStage);
     }
 
     // epilogue
@@ -287,30 +311,64 @@ __global__ void __launch_bounds__(kThreads, 2) ld_gemm_kernel(LargeDParams p, Ge
             for (int i = 0; i < 16; ++i) c[tm][tn][i] = 0.f;
     // Operand tiles go straight from global memory into the LDS stage that was last read one
     // step ago.  Rows of B past n repeat the last row; they meet columns (rows, if A is read
-    // transposed) of A that are zero.
+    // transposed) of A that are zero.  Lane offsets of the copies and of the fragment reads are
+    // computed once; the k-loop runs two steps per iteration so that the stage offsets are
+    // immediates (its trip count is a multiple of 8: all bounds are multiples of 256).
+    TileLoader<TM, BK> copy_at;   // A read transposed: BK rows of TM columns
+    TileLoader<BK, TM> copy_a;    // A as stored: TM rows of BK columns
+    TileLoader<128, BK> copy_b;
+    if (A_KMAJOR) copy_at.init(tid, p.npad);
+    else copy_a.init(tid, p.npad);
+    copy_b.init(tid, p.stride_n);
     auto fetch = [&](int k, int stage) {
         char* at = smem + stage * kStage;
-        if (A_KMAJOR) load_tile_direct<TM, BK>(gA + m0, p.npad, k, p.npad, at, tid);
-        else load_tile_direct<BK, TM>(gA + k, p.npad, m0, p.npad, at, tid);
-        load_tile_direct<128, BK>(gB + n0, p.stride_n, k, p.n, at + kTileA, tid);
+        if (A_KMAJOR) copy_at.load(gA + m0 + (long)k * p.npad, at);
+        else copy_a.load(gA + k + (long)m0 * p.npad, at);
+        copy_b.load(gB + n0, p.stride_n, k, p.n, at + kTileA, tid);
     };
+    // A read transposed: one register pair per 32-row tile t.  A as stored: one register per
+    // 16-byte chunk of this lane's row (the 32-row tiles are immediates apart).
+    int ra[4][2], rc[4], rb[2][2];
+    {
+        FragOffsets<TM> fa;
+        FragOffsets<128> fb;
+        fa.init(lane);
+        fb.init(lane);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            ra[t][0] = fa.tr(4 * wm + t, 0);
+            ra[t][1] = fa.tr(4 * wm + t, 1);
+            rc[t] = tile_off<BK>(128 * wm + l32, t) + 8 * h;
+        }
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int half = 0; half < 2; ++half) rb[t][half] = fb.tr(2 * wn + t, half) + kTileA;
+    }
     fetch(k_begin, 0);
     wait_direct_loads();
     __syncthreads();
-    int stage = 0;
-    for (int k = k_begin; k < k_end; k += BK, stage ^= 1) {
-        if (k + BK < k_end) fetch(k + BK, stage ^ 1);
-        const char* at = smem + stage * kStage;
-        const char* bt = at + kTileA;
+    auto step = [&](int k, auto stage_off) {
+        constexpr int so = decltype(stage_off)::value;
+        if (k + BK < k_end) fetch(k + BK, so == 0 ? 1 : 0);
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
             bf16x8 a[4], b[2];
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
-                a[t] = A_KMAJOR ? load_frag_t<TM>(at, 128 * wm + 32 * t, 16 * ks, lane)
-                                : load_frag_perm<BK>(at, 128 * wm + 32 * t, ks, lane);
+            for (int t = 0; t < 4; ++t) {
+                if (A_KMAJOR) {
+                    a[t] = FragOffsets<TM>::read_t(smem, ra[t][0], ra[t][1], 16 * ks, so);
+                } else {
+                    // k order of the transposed reads: 8-byte halves of chunks 2 ks and 2 ks + 1
+                    const int imm = so + 32 * t * (BK * 2);
+                    const u32x2 lo = *reinterpret_cast<const u32x2*>(smem + rc[2 * ks] + imm);
+                    const u32x2 hi = *reinterpret_cast<const u32x2*>(smem + rc[2 * ks + 1] + imm);
+                    const u32x4 r = {lo[0], lo[1], hi[0], hi[1]};
+                    a[t] = __builtin_bit_cast(bf16x8, r);
+                }
+            }
 #pragma unroll
-            for (int t = 0; t < 2; ++t) b[t] = load_frag_t<128>(bt, 64 * wn + 32 * t, 16 * ks, lane);
+            for (int t = 0; t < 2; ++t) b[t] = FragOffsets<128>::read_t(smem, rb[t][0], rb[t][1], 16 * ks, so);
 #pragma unroll
             for (int tm = 0; tm < 4; ++tm)
 #pragma unroll
@@ -318,6 +376,10 @@ __global__ void __launch_bounds__(kThreads, 2) ld_gemm_kernel(LargeDParams p, Ge
         }
         wait_direct_loads();
         __syncthreads();
+    };
+    for (int k = k_begin; k < k_end; k += 2 * BK) {
+        step(k, std::integral_constant<int, 0>{});
+        step(k + BK, std::integral_constant<int, kStage>{});
     }
     // accumulator: lane <-> output column, register <-> output row
 #pragma unroll
