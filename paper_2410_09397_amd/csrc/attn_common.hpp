@@ -52,6 +52,10 @@ __device__ __forceinline__ bf16x8 acc_to_operand(const f32x16& c, int s) {
     return __builtin_bit_cast(bf16x8, r);
 }
 
+__device__ __forceinline__ float max3(float a, float b, float c) {
+    return __builtin_elementwise_maximum(a, __builtin_elementwise_maximum(b, c));
+}
+
 // ---------------------------------------------------------------------------------------
 // LDS tile: R rows of D bf16, row-major, no padding, 16-byte chunks XOR-swizzled by row so
 // that both fetch patterns below spread over all 64 banks:

@@ -125,15 +125,27 @@ __global__ void __launch_bounds__(kThreads, 2) fwd_kernel(FusedParams p) {
                     st[T][i] = (32 * T + 8 * (i >> 2) + (i & 3) > lim) ? -__builtin_inff() : st[T][i];
         }
         // maximum (IEEE-754-2019, v_maximum3_f32) instead of fmaxf: for fmaxf the compiler first
-        // canonicalises every accumulator value (one extra VALU instruction each, for signalling NaNs)
-        float mx = __builtin_elementwise_maximum(st[0][0], st[1][0]);
+        // canonicalises every accumulator value (one extra VALU instruction each, for signalling
+        // NaNs).  Two chains of three-input maxima over the 32 values of this lane.
+        float mxa = max3(st[0][0], st[0][1], st[0][2]), mxb = max3(st[1][0], st[1][1], st[1][2]);
 #pragma unroll
-        for (int i = 1; i < 16; ++i)
-            mx = __builtin_elementwise_maximum(mx, __builtin_elementwise_maximum(st[0][i], st[1][i]));
+        for (int i = 3; i < 15; i += 2) {
+            mxa = max3(mxa, st[0][i], st[0][i + 1]);
+            mxb = max3(mxb, st[1][i], st[1][i + 1]);
+        }
+        float mx = max3(mxa, mxb, __builtin_elementwise_maximum(st[0][15], st[1][15]));
         mx = __builtin_elementwise_maximum(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run, mx * cs);
+        // The reference point m_run of the exponentials only has to be close to the row maximum,
+        // not equal to it: it moves (and O, l are rescaled) only when the maximum has grown by
+        // more than kSlack, so p = exp2(s - m_run) stays below 2^kSlack and the final O / l and
+        // m_run + log2(l) are unchanged.  After the first tiles of a row this almost never
+        // happens, which saves the 4 MT + 1 multiplications per lane and tile of the rescaling.
+        constexpr float kSlack = 8.f;
+        const float cand = mx * cs;
+        const bool grow = cand > m_run + kSlack;  // also the first finite maximum after -inf
+        const float m_new = grow ? cand : m_run;
         const float m_use = (m_new == -__builtin_inff()) ? 0.f : m_new;  // nothing visible yet
-        if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {  // some row's maximum moved: rescale
+        if (__builtin_amdgcn_ballot_w64(grow) != 0) {  // some row's reference moved: rescale
             const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
             l_run *= alpha;
 #pragma unroll
