@@ -103,10 +103,12 @@ __global__ void __launch_bounds__(kThreads, 2) wgrad_partial_kernel(const __bf16
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[x][y][i] = 0.f;
 
+    TileLoader<D, BR> loader;
+    loader.init(tid, D);
     auto fetch = [&](int it, int stage) {
         char* s = smem + stage * kStageBytes;
-        load_tile_direct<D, BR>(a_head, D, r_begin + it * BR, n, s, tid);
-        load_tile_direct<D, BR>(q_head, D, r_begin + it * BR, n, s + kTileBytes, tid);
+        loader.load(a_head, D, r_begin + it * BR, n, s, tid);
+        loader.load(q_head, D, r_begin + it * BR, n, s + kTileBytes, tid);
     };
     if (n_it > 0) fetch(0, 0);
     wait_direct_loads();

@@ -18,9 +18,9 @@ import os
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 COPY_BYTES = float(1 << 30)  # bytes read, and bytes written, by the calibration copy
-BWD_KERNELS = ("delta_kernel", "bwd_dkdv", "bwd_dq", "ld_scores_kernel<2>", "ld_gemm_kernel", "generic_delta",
+BWD_KERNELS = ("delta_kernel", "bwd_dkdv", "bwd_dq", "ld_scores_kernel<2,", "ld_gemm_kernel", "generic_delta",
                "generic_dq", "generic_dkdv")
-FWD_KERNELS = ("fwd_kernel", "ld_scores_kernel<0>", "ld_scores_kernel<1>", "ld_lse_combine", "generic_fwd")
+FWD_KERNELS = ("fwd_kernel", "ld_scores_kernel<0,", "ld_scores_kernel<1,", "ld_lse_combine", "generic_fwd")
 
 
 def _one(pattern):
