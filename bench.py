@@ -53,6 +53,21 @@ def load_traffic(name):
         return json.load(fh).get(name)
 
 
+def mfma_ceiling(attn, torch, zero_operands, ms_target=60.0):
+    """Rate and clock of the library's register-only MFMA loop, run for about ms_target."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    iters = 20000
+    for _ in range(2):  # the second run is sized from the first
+        e0.record()
+        clock, flops = attn.attn_mfma_ceiling(iters, zero_operands)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        last = {"tflops": flops / (ms * 1e-3) * 1e-12, "clock_ghz": float(clock.item()), "ms": ms, "iters": iters}
+        iters = max(1000, int(iters * ms_target / ms))
+    return last
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -70,12 +85,22 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy, so that HBM byte counters read in the "
                          "same profiler run can be scaled by a transfer of known size")
+    ap.add_argument("--mfma-ceiling", action="store_true",
+                    help="diagnostic: time the register-only MFMA loop of the library on random and on zero "
+                         "operands (the power-limited ceiling of the matrix pipe), print one JSON line and exit")
+    ap.add_argument("--zero-operands", action="store_true",
+                    help="diagnostic: run the workload on all-zero Q, K, V, dO (same instruction stream, no "
+                         "switching activity); the line is marked and is not a benchmark result")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
 
     import torch
     from paper_2410_09397_amd import attn, io_bound, synth
+    if args.mfma_ceiling:
+        print(json.dumps({"probe": "mfma_ceiling", "unit": "TFLOP/s", "nominal_peak": PEAK_TFLOPS["bf16"],
+                          **{kind: mfma_ceiling(attn, torch, zero) for kind, zero in (("random", False), ("zeros", True))}}))
+        return
     w = synth.workload(args.workload)
     if args.shape:
         w = synth.reshaped(w, args.shape)
@@ -84,6 +109,9 @@ def main():
     dt = {"bf16": torch.bfloat16, "f32": torch.float32}[w.dtype]
     inp = synth.make_inputs(w)
     Q, K, V, dO = (torch.from_numpy(inp[t]).to("cuda").to(dt) for t in ("Q", "K", "V", "dO"))
+    if args.zero_operands:
+        for t in (Q, K, V, dO):
+            t.zero_()
     mask = attn.BlockMask(inp["keep"], w.block, w.n) if w.sparse else None
     O = torch.empty_like(Q)
     LSE = torch.empty(Q.shape[:3], dtype=torch.float32, device="cuda")
@@ -129,7 +157,8 @@ def main():
     out = {
         "metric": METRIC, "value": bwd_tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "vs_baseline": None, "dtype": w.dtype,
+        "data": "all-zero operands (diagnostic, not a benchmark result)" if args.zero_operands else "synthetic",
         "config": {"workload": w.name, "batch": w.batch, "heads": w.heads, "n": w.n, "d": w.d,
                    "causal": w.causal, "block_sparse": w.sparse, "step": "attn_fwd + attn_bwd"},
         "bwd_ms": bwd_ms, "fwd_ms": fwd_ms, "fwd_tflops": w.fwd_flops() / (fwd_ms * 1e-3) * 1e-12,
@@ -140,6 +169,10 @@ def main():
         "io_bound": bound,
         "traffic_over_yardstick": (traffic / bound["yardstick_bytes"]) if traffic else None,
     }
+    if w.dtype == "bf16":
+        # context for `frac`: what a register-only MFMA loop sustains on this GPU for random operands
+        # (the clock under matrix load follows the power the data draws; `peak` assumes 2.4 GHz)
+        out["mfma_ceiling_random_operands"] = mfma_ceiling(attn, torch, False, ms_target=40.0)
     if args.wgrad and w.dtype == "bf16" and w.d in (64, 128) and not w.sparse:
         del grads, O, ws
         wi = synth.make_wgrad_inputs(w)

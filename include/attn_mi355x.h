@@ -122,6 +122,22 @@ attn_status attn_blockmask_validate(int32_t block, int32_t nblk, int32_t n,
                                     const int32_t *row_ptr, const int32_t *col_idx,
                                     const int32_t *col_ptr, const int32_t *row_idx);
 
+/*
+ * Measurement aid (no part of the attention path; the paper has no counterpart): launches a
+ * register-only loop of independent dense bf16 MFMAs (32x32x16) on every CU, two waves per SIMD,
+ * `iters` iterations of 8 MFMAs per wave, on random (zero_operands = 0) or all-zero operands.
+ * The rate it sustains is the ceiling of any kernel built on that instruction for operands of
+ * that kind: under matrix load the shader clock follows the power the data's switching activity
+ * draws.  Asynchronous on `stream`; the caller times it.
+ *   clock_ghz  DEVICE float[1], caller owned: shader clock seen by one workgroup over the run
+ *              (cycle counter against the 100 MHz constant-rate counter), valid after the stream
+ *              has been synchronised
+ *   flops      HOST double[1]: floating-point operations the launch executes
+ * Errors: ATTN_ERR_INVALID_ARG (iters < 1, null pointers), ATTN_ERR_DEVICE.
+ */
+attn_status attn_mfma_ceiling(int32_t iters, int32_t zero_operands, float *clock_ghz, double *flops,
+                              void *stream);
+
 /* Static description of a status code. */
 const char *attn_status_str(attn_status s);
 

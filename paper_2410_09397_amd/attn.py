@@ -17,7 +17,8 @@ ATTN_OK, ATTN_ERR_INVALID_ARG, ATTN_ERR_UNSUPPORTED, ATTN_ERR_WORKSPACE, ATTN_ER
 ATTN_F32, ATTN_BF16 = 0, 1
 
 EXPORTS = ("attn_workspace_bytes", "attn_fwd", "attn_bwd", "attn_bwd_blocksparse",
-           "attn_wgrad_workspace_bytes", "attn_bwd_wgrad", "attn_blockmask_validate", "attn_status_str")
+           "attn_wgrad_workspace_bytes", "attn_bwd_wgrad", "attn_blockmask_validate", "attn_mfma_ceiling",
+           "attn_status_str")
 
 
 class attn_desc(ctypes.Structure):
@@ -65,6 +66,8 @@ def lib():
         L.attn_bwd_wgrad.argtypes = [dp] + [vp] * 7 + [vp, ctypes.c_size_t, vp]
         L.attn_blockmask_validate.restype = ctypes.c_int
         L.attn_blockmask_validate.argtypes = [ctypes.c_int32] * 3 + [i32p] * 4
+        L.attn_mfma_ceiling.restype = ctypes.c_int
+        L.attn_mfma_ceiling.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.attn_status_str.restype = ctypes.c_char_p
         L.attn_status_str.argtypes = [ctypes.c_int]
         _lib = L
@@ -212,3 +215,17 @@ def attn_bwd_wgrad(A1, A2, A3, X, Y, dO, scale=1.0, causal=False, stream=None, o
     if st != ATTN_OK:
         raise AttnError(st, "attn_bwd_wgrad")
     return g
+
+
+def attn_mfma_ceiling(iters, zero_operands=False, stream=None):
+    """Launches the register-only MFMA loop (include/attn_mi355x.h).  Returns (clock, flops): a
+    device float tensor that holds the shader clock in GHz once the stream is synchronised, and
+    the number of floating-point operations of the launch."""
+    import torch
+    clock = torch.zeros(1, dtype=torch.float32, device="cuda")
+    flops = ctypes.c_double(0.0)
+    st = lib().attn_mfma_ceiling(int(iters), int(bool(zero_operands)), clock.data_ptr(), ctypes.byref(flops),
+                                 _stream(stream))
+    if st != ATTN_OK:
+        raise AttnError(st, "attn_mfma_ceiling")
+    return clock, flops.value
