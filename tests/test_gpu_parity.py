@@ -29,6 +29,10 @@ CASES = [
     W("bf16_d128_causal", 31, 1, 2, 512, 128, "bf16", causal=True, dO_std=0.1),
     W("bf16_d128_ragged", 32, 1, 3, 200, 128, "bf16"),
     W("bf16_d128_8heads", 33, 2, 4, 256, 128, "bf16", causal=True),
+    # odd numbers of streamed tiles (the mask-free tiles run two at a time, one is left over)
+    W("bf16_d128_5tiles", 34, 1, 2, 320, 128, "bf16"),
+    W("bf16_d64_7tiles_causal", 35, 1, 2, 448, 64, "bf16", causal=True),
+    W("bf16_d128_9tiles_ragged", 36, 1, 1, 570, 128, "bf16"),
     # block-sparse, 128 x 128 blocks
     W("bf16_d128_sparse", 41, 1, 2, 1024, 128, "bf16", sparse=True, extra_frac=0.3),
     W("bf16_d128_sparse_ragged", 42, 1, 1, 1000, 128, "bf16", sparse=True, extra_frac=0.15),
