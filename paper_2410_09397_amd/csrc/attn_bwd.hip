@@ -115,14 +115,17 @@ __global__ void __launch_bounds__(kThreads, 2) bwd_dkdv_kernel(FusedParams p) {
     bool row_ok = false;
     TileLoader<D, BR> loader;
     loader.init(tid, ld);
-    auto fetch = [&](int i0, int stage_off) {
-        char* s = smem + stage_off;
-        loader.load(p.Q + base, ld, i0, p.n, s, tid);
-        loader.load(p.dO + base, ld, i0, p.n, s + kTileBytes, tid);
+    auto fetch_rows = [&](int i0) {
         const int q = i0 + 32 * wx + l32;
         row_ok = q < p.n;
         lse_raw = lse_g[min(q, p.n - 1)];
         delta_raw = delta_g[min(q, p.n - 1)];
+    };
+    auto fetch = [&](int i0, int stage_off) {
+        char* s = smem + stage_off;
+        loader.load(p.Q + base, ld, i0, p.n, s, tid);
+        loader.load(p.dO + base, ld, i0, p.n, s + kTileBytes, tid);
+        fetch_rows(i0);
     };
     int i0_next = n_it > 0 ? tile_start(0) : 0;
     if (n_it > 0) fetch(i0_next, 0);
@@ -170,9 +173,24 @@ __global__ void __launch_bounds__(kThreads, 2) bwd_dkdv_kernel(FusedParams p) {
         const float lse_cur = row_ok ? lse_raw * kLog2e : __builtin_inff();
         const float delta_cur = row_ok ? delta_raw : 0.f;
         const int q_off = stage_off;  // Q tile; the dO tile follows it
+        // The copies of the next tile go into the stage that was last read before barrier B of the
+        // previous tile.  In the mask-free body they are issued one by one between the MFMAs of
+        // phase 1 (a wave that issues all of them at once waits until the copy path, 64 B per
+        // cycle and CU, has taken them: ~750 cycles per tile in front of the first MFMA; 1.5 % faster).
+        bool spread = false;
+        const __bf16* next_q = nullptr;
+        const __bf16* next_g = nullptr;
+        char* next_stage = smem + (kStageBytes - q_off);
         if (it + 1 < n_it) {
             i0_next = tile_start(it + 1);
-            fetch(i0_next, kStageBytes - q_off);  // that stage was last read before barrier B
+            spread = !decltype(masked)::value && !skip && i0_next + BR <= p.n;
+            if (spread) {
+                next_q = p.Q + base + (long)i0_next * ld;
+                next_g = p.dO + base + (long)i0_next * ld;
+                fetch_rows(i0_next);
+            } else {
+                fetch(i0_next, kStageBytes - q_off);
+            }
         }
         __builtin_amdgcn_s_setprio(kPrioPhase1);
         if (!skip) {
@@ -201,6 +219,12 @@ __global__ void __launch_bounds__(kThreads, 2) bwd_dkdv_kernel(FusedParams p) {
                     }
                     s = mfma32(kf[ks], fq[ks], s);
                     dp = mfma32(vf[ks], fg[ks], dp);
+                    if (spread) {  // 2 kInst copies over KS k-steps: one per step for d = 64 and 128
+                        constexpr int kPer = TileLoader<D, BR>::kInst;
+                        static_assert(2 * kPer == KS, "one copy per k-step");
+                        if (ks < kPer) loader.load_one(ks, next_q, next_stage);
+                        else loader.load_one(ks - kPer, next_g, next_stage + kTileBytes);
+                    }
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
