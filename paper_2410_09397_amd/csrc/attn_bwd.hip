@@ -350,6 +350,19 @@ __global__ void __launch_bounds__(kThreads, QT == 1 ? 2 : 1) bwd_dq_kernel(Fused
     }
     auto tile_start = [&](int it) -> int { return tile_start_row<BC>(p.list_idx, lp0, 0, it); };
 
+    // K and V tiles go straight from global memory into the LDS stage that was last read one
+    // iteration ago; rows past n repeat the last row and are masked below.
+    TileLoader<D, BC> loader;
+    loader.init(tid, ld);
+    auto fetch = [&](int j0, int stage) {
+        char* s = smem + stage * kStageBytes;
+        loader.load(p.K + base, ld, j0, p.n, s, tid);
+        loader.load(p.V + base, ld, j0, p.n, s + kTileBytes, tid);
+    };
+    // the first tile is requested before the resident rows, so that the two latencies overlap
+    int j0_next = n_it > 0 ? tile_start(0) : 0;
+    if (n_it > 0) fetch(j0_next, 0);
+
     // resident operands: QT tiles of 32 queries per wave
     int q[QT];
     bf16x8 qf[QT][KS], gf[QT][KS];
@@ -410,17 +423,6 @@ __global__ void __launch_bounds__(kThreads, QT == 1 ? 2 : 1) bwd_dq_kernel(Fused
     lane_offsets.init(lane);
     FragAddrs<D> fo;
     fo.init(lane_offsets);
-    // K and V tiles go straight from global memory into the LDS stage that was last read one
-    // iteration ago; rows past n repeat the last row and are masked below.
-    TileLoader<D, BC> loader;
-    loader.init(tid, ld);
-    auto fetch = [&](int j0, int stage) {
-        char* s = smem + stage * kStageBytes;
-        loader.load(p.K + base, ld, j0, p.n, s, tid);
-        loader.load(p.V + base, ld, j0, p.n, s + kTileBytes, tid);
-    };
-    int j0_next = n_it > 0 ? tile_start(0) : 0;
-    if (n_it > 0) fetch(j0_next, 0);
     wait_direct_loads();
     __syncthreads();
 
