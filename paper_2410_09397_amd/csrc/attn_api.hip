@@ -25,7 +25,7 @@ attn_status check_desc(const attn_desc* d) {
     if (d->causal != 0 && d->causal != 1) return ATTN_ERR_INVALID_ARG;
     if (!std::isfinite(d->scale)) return ATTN_ERR_INVALID_ARG;
     if (d->dtype != ATTN_F32 && d->dtype != ATTN_BF16) return ATTN_ERR_UNSUPPORTED;
-    if (d->d > 512) return ATTN_ERR_UNSUPPORTED;
+    if (d->d > 512 && !(d->dtype == ATTN_BF16 && d->d == 1024)) return ATTN_ERR_UNSUPPORTED;
     if (d->dtype == ATTN_BF16 && d->d % 8 != 0) return ATTN_ERR_UNSUPPORTED;
     if (d->stride_n < d->d || d->stride_h < 0 || d->stride_b < 0) return ATTN_ERR_INVALID_ARG;
     if (d->dtype == ATTN_BF16 && (d->stride_n % 8 || d->stride_h % 8 || d->stride_b % 8))
@@ -47,8 +47,14 @@ bool is_empty(const attn_desc* d) { return (long)d->batch * d->heads * d->n == 0
 
 Path pick_path(const attn_desc* d, const attn_blockmask* m) {
     if (d->dtype == ATTN_BF16 && (d->d == 64 || d->d == 128) && (!m || m->block == 128)) return Path::kFused;
-    if (d->dtype == ATTN_BF16 && (d->d == 256 || d->d == 512) && !m && d->n <= 32768) return Path::kLargeD;
+    if (d->dtype == ATTN_BF16 && (d->d == 256 || d->d == 512 || d->d == 1024) && !m && d->n <= 32768)
+        return Path::kLargeD;
     return Path::kGeneric;
+}
+
+// d = 1024 exists on the large-d path only (the generic kernels stop at 512).
+attn_status check_path(const attn_desc* d, const attn_blockmask* m) {
+    return (d->d > 512 && pick_path(d, m) != Path::kLargeD) ? ATTN_ERR_UNSUPPORTED : ATTN_OK;
 }
 
 size_t delta_bytes(const attn_desc* d) { return round_up((size_t)d->batch * d->heads * d->n * sizeof(float), 256); }
@@ -119,6 +125,8 @@ attn_status bwd_impl(const attn_desc* desc, const attn_blockmask* mask, const vo
     attn_status st = check_desc(desc);
     if (st != ATTN_OK) return st;
     st = check_mask(desc, mask);
+    if (st != ATTN_OK) return st;
+    st = check_path(desc, mask);
     if (st != ATTN_OK) return st;
     if (is_empty(desc)) return ATTN_OK;
     if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV) return ATTN_ERR_INVALID_ARG;
@@ -223,7 +231,7 @@ WgradLayout wgrad_layout(const attn_desc* d) {
 extern "C" {
 
 size_t attn_workspace_bytes(const attn_desc* desc, const attn_blockmask* mask) {
-    if (check_desc(desc) != ATTN_OK || check_mask(desc, mask) != ATTN_OK) return 0;
+    if (check_desc(desc) != ATTN_OK || check_mask(desc, mask) != ATTN_OK || check_path(desc, mask) != ATTN_OK) return 0;
     if (is_empty(desc)) return 256;
     if (pick_path(desc, mask) == Path::kLargeD) {
         const size_t bwd = delta_bytes(desc) + 2 * nn_bytes(desc);
@@ -238,6 +246,8 @@ attn_status attn_fwd(const attn_desc* desc, const attn_blockmask* mask, const vo
     attn_status st = check_desc(desc);
     if (st != ATTN_OK) return st;
     st = check_mask(desc, mask);
+    if (st != ATTN_OK) return st;
+    st = check_path(desc, mask);
     if (st != ATTN_OK) return st;
     if (is_empty(desc)) return ATTN_OK;
     if (!Q || !K || !V || !O || !LSE) return ATTN_ERR_INVALID_ARG;

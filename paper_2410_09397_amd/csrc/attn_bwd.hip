@@ -15,24 +15,28 @@
 namespace attn {
 
 // --------------------------------------------------------------------------------- delta
-// d / 8 consecutive lanes share one row (16-byte chunks, all 64 lanes busy for d <= 512); the row
-// sum is a shuffle reduction inside that lane group.  d / 8 must be a power of two <= 64.
+// min(d / 8, 64) consecutive lanes share one row (16-byte chunks; a lane takes every 64th chunk when
+// the row has more than 64); the row sum is a shuffle reduction inside that lane group.  d / 8 must
+// be a power of two.
 __global__ void __launch_bounds__(kThreads) delta_kernel(FusedParams p, int d) {
-    const int cpr = d >> 3;  // chunks (lanes) per row
+    const int cpr = d >> 3;             // chunks per row
+    const int lpr = cpr < 64 ? cpr : 64;  // lanes per row
     const long rows = (long)p.batch * p.heads * p.n;
     const long f = (long)blockIdx.x * kThreads + threadIdx.x;
-    const long r = f / cpr;
-    const int c = (int)(f % cpr);
+    const long r = f / lpr;
+    const int c = (int)(f % lpr);
     float acc = 0.f;
     if (r < rows) {
         const int bh = (int)(r / p.n), i = (int)(r % p.n);
-        const long off = (long)(bh / p.heads) * p.stride_b + (long)(bh % p.heads) * p.stride_h + (long)i * p.stride_n + c * 8;
-        const bf16x8 o = *reinterpret_cast<const bf16x8*>(p.O + off);
-        const bf16x8 g = *reinterpret_cast<const bf16x8*>(p.dO + off);
+        const long off = (long)(bh / p.heads) * p.stride_b + (long)(bh % p.heads) * p.stride_h + (long)i * p.stride_n;
+        for (int cc = c; cc < cpr; cc += lpr) {
+            const bf16x8 o = *reinterpret_cast<const bf16x8*>(p.O + off + cc * 8);
+            const bf16x8 g = *reinterpret_cast<const bf16x8*>(p.dO + off + cc * 8);
 #pragma unroll
-        for (int t = 0; t < 8; ++t) acc += (float)o[t] * (float)g[t];
+            for (int t = 0; t < 8; ++t) acc += (float)o[t] * (float)g[t];
+        }
     }
-    for (int m = cpr >> 1; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
+    for (int m = lpr >> 1; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
     if (r < rows && c == 0) p.delta[r] = acc;
 }
 
@@ -547,7 +551,7 @@ __global__ void __launch_bounds__(kThreads, QT == 1 ? 2 : 1) bwd_dq_kernel(Fused
 
 // ------------------------------------------------------------------------------ launchers
 void launch_delta(const FusedParams& p, int d, hipStream_t stream) {
-    const long lanes = (long)p.batch * p.heads * p.n * (d / 8);
+    const long lanes = (long)p.batch * p.heads * p.n * (d / 8 < 64 ? d / 8 : 64);
     hipLaunchKernelGGL(delta_kernel, dim3((unsigned)((lanes + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream, p, d);
 }
 

@@ -43,6 +43,8 @@ CASES = [
     W("bf16_d256", 53, 1, 2, 256, 256, "bf16"),
     W("bf16_d512_causal_5blocks", 54, 1, 2, 640, 512, "bf16", causal=True, dO_std=0.1),
     W("bf16_d256_ragged_causal", 55, 2, 1, 333, 256, "bf16", causal=True),
+    W("bf16_d1024", 58, 1, 1, 256, 1024, "bf16"),
+    W("bf16_d1024_ragged_causal", 59, 1, 2, 150, 1024, "bf16", causal=True),
     # shapes only the generic fp32-FMA kernels take: bf16 with d outside {64,128,256,512},
     # d = 512 under a block mask, and a block edge other than 128
     W("bf16_d96_generic", 56, 1, 2, 150, 96, "bf16", causal=True),

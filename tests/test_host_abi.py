@@ -61,7 +61,9 @@ def call_bwd(d, ptrs=(P,) * 9, ws=P, ws_bytes=1 << 30):
     (dict(stride_n=32), attn.ATTN_ERR_INVALID_ARG),
     (dict(stride_n=68), attn.ATTN_ERR_INVALID_ARG),      # bf16 rows must stay 16-byte aligned
     (dict(dtype=7), attn.ATTN_ERR_UNSUPPORTED),
-    (dict(d=1024, stride_n=1024), attn.ATTN_ERR_UNSUPPORTED),
+    (dict(d=2048, stride_n=2048), attn.ATTN_ERR_UNSUPPORTED),
+    (dict(d=1024, stride_n=1024, dtype=attn.ATTN_F32), attn.ATTN_ERR_UNSUPPORTED),  # bf16 large-d path only
+    (dict(d=768, stride_n=768), attn.ATTN_ERR_UNSUPPORTED),
     (dict(stride_n=1 << 22), attn.ATTN_ERR_UNSUPPORTED),   # row offsets inside a tile are 32-bit
     (dict(d=60, stride_n=64), attn.ATTN_ERR_UNSUPPORTED),  # bf16 needs d % 8 == 0
 ])
