@@ -27,8 +27,8 @@
  *     nothing and leaves outputs untouched.  batch * heads * n == 0 is a valid empty call.
  *   - Supported: d a multiple of 8 for ATTN_BF16 (pointers and strides 16-byte aligned), any d
  *     for ATTN_F32, 1 <= d <= 512.  ATTN_BF16 runs bf16-MFMA kernels with fp32 accumulation for
- *     d in {64, 128} (block masks: block == 128; fused, nothing n x n leaves the chip) and for
- *     d in {256, 512, 1024} without block mask and n <= 32768 (four-phase path through the
+ *     d in {64, 128, 256} (block masks: block == 128; fused, nothing n x n leaves the chip) and
+ *     for d in {512, 1024} without block mask and n <= 32768 (four-phase path through the
  *     workspace; d = 1024 is supported there only); every other supported case, ATTN_F32 always,
  *     runs fp32 FMA kernels.
  */

@@ -46,8 +46,9 @@ attn_status check_mask(const attn_desc* d, const attn_blockmask* m) {
 bool is_empty(const attn_desc* d) { return (long)d->batch * d->heads * d->n == 0; }
 
 Path pick_path(const attn_desc* d, const attn_blockmask* m) {
-    if (d->dtype == ATTN_BF16 && (d->d == 64 || d->d == 128) && (!m || m->block == 128)) return Path::kFused;
-    if (d->dtype == ATTN_BF16 && (d->d == 256 || d->d == 512 || d->d == 1024) && !m && d->n <= 32768)
+    if (d->dtype == ATTN_BF16 && (d->d == 64 || d->d == 128 || d->d == 256) && (!m || m->block == 128))
+        return Path::kFused;
+    if (d->dtype == ATTN_BF16 && (d->d == 512 || d->d == 1024) && !m && d->n <= 32768)
         return Path::kLargeD;
     return Path::kGeneric;
 }

@@ -1,4 +1,5 @@
-// Fused backward kernels for d <= 128 (the regime where a d x d working set fits on chip):
+// Fused backward kernels for d <= 256 (the regime where a d x d working set fits on chip; d = 256
+// runs with one wave per SIMD and up to 512 registers per lane):
 //   dQ      : one workgroup owns a block of 128 queries and streams key tiles; its prologue also
 //             forms delta = rowsum(dO o O) (second matrix form of p, App. B.4) for those queries
 //   dK, dV  : one workgroup owns a block of 64 keys and streams query tiles
@@ -57,7 +58,7 @@ __global__ void __launch_bounds__(kThreads) delta_kernel(FusedParams p, int d) {
 // (measured: 3-4 % faster).
 constexpr int kPrioPhase1 = 3, kPrioSoftmax = 1, kPrioPhase2 = 0;
 template <int D>
-__global__ void __launch_bounds__(kThreads, 2) bwd_dkdv_kernel(FusedParams p) {
+__global__ void __launch_bounds__(kThreads, D <= 128 ? 2 : 1) bwd_dkdv_kernel(FusedParams p) {
     constexpr int BR = 64, BC = 64, KS = D / 16, MT = D / 32;
     constexpr int kTileBytes = BR * D * 2;
     constexpr int kStageBytes = 2 * kTileBytes;
@@ -333,7 +334,7 @@ __global__ void __launch_bounds__(kThreads, 2) bwd_dkdv_kernel(FusedParams p) {
 //   dS^T = P^T (dP^T - delta)                        per-lane scalars lse2, delta
 //   dQ_w^T += K_T^T dS^T                             K^T from transposed LDS reads
 template <int D, int QT>
-__global__ void __launch_bounds__(kThreads, QT == 1 ? 2 : 1) bwd_dq_kernel(FusedParams p) {
+__global__ void __launch_bounds__(kThreads, QT == 1 && D <= 128 ? 2 : 1) bwd_dq_kernel(FusedParams p) {
     constexpr int BR = 128 * QT, BC = 64, KS = D / 16, MT = D / 32;
     constexpr int kTileBytes = BC * D * 2;
     constexpr int kStageBytes = 2 * kTileBytes;
@@ -593,6 +594,7 @@ hipError_t launch_bwd_fused(int d, const FusedParams& p, const int32_t* csr_ptr,
     switch (d) {
         case 64: return launch_bwd<64>(p, csr_ptr, csr_idx, csc_ptr, csc_idx, stream, dq_only);
         case 128: return launch_bwd<128>(p, csr_ptr, csr_idx, csc_ptr, csc_idx, stream, dq_only);
+        case 256: return launch_bwd<256>(p, csr_ptr, csr_idx, csc_ptr, csc_idx, stream, dq_only);
         default: return hipErrorInvalidValue;
     }
 }

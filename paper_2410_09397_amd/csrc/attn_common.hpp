@@ -239,8 +239,17 @@ struct TileLoader {
         }
         lds0 = (unsigned)w * 1024u;
     }
+    // The scalar base of the copy instructions: the address is uniform, but the compiler has to
+    // be told so where it cannot prove it (it then hands the assembler a vector register pair).
+    static __device__ __forceinline__ const __bf16* uniform(const __bf16* ptr) {
+        const unsigned long long a = reinterpret_cast<unsigned long long>(ptr);
+        const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)a);
+        const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(a >> 32));
+        return reinterpret_cast<const __bf16*>(((unsigned long long)hi << 32) | lo);
+    }
     // first_row: address of the tile's first row (uniform); all ROWS rows must exist
-    __device__ __forceinline__ void load(const __bf16* first_row, char* tile) const {
+    __device__ __forceinline__ void load(const __bf16* first_row_in, char* tile) const {
+        const __bf16* first_row = uniform(first_row_in);
         const unsigned t0 =
             __builtin_amdgcn_readfirstlane((unsigned)(size_t)(ATTN_LDS char*)tile) + lds0;
 #pragma unroll
@@ -253,7 +262,8 @@ struct TileLoader {
         }
     }
     // copy instruction u of load() on its own, for callers that spread the copies over their MFMAs
-    __device__ __forceinline__ void load_one(int u, const __bf16* first_row, char* tile) const {
+    __device__ __forceinline__ void load_one(int u, const __bf16* first_row_in, char* tile) const {
+        const __bf16* first_row = uniform(first_row_in);
         const unsigned dst =
             __builtin_amdgcn_readfirstlane((unsigned)(size_t)(ATTN_LDS char*)tile) + lds0 + u * NW * 1024;
         asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(dst), "v"(voff[u]), "s"(first_row));

@@ -1,4 +1,4 @@
-// Fused forward for d <= 128: O = diag(l)^{-1} exp(scale Q K^T) V and LSE = log l (forward
+// Fused forward for d <= 256 (d = 256: one wave per SIMD): O = diag(l)^{-1} exp(scale Q K^T) V and LSE = log l (forward
 // definition, Sec. 3.1; A, l, f, O of App. B.4), evaluated per block of 128 queries with a
 // running maximum so that no n x n matrix is formed.  The paper gives no forward algorithm;
 // the streaming-softmax tiling is prior art, the kernel is written for gfx950.
@@ -16,7 +16,7 @@ namespace attn {
 //            see the same maximum; their partial sums are added at the end)
 //   O_w^T += V_T^T P^T                 V^T from transposed LDS reads, P^T straight from registers
 template <int D>
-__global__ void __launch_bounds__(kThreads, 2) fwd_kernel(FusedParams p) {
+__global__ void __launch_bounds__(kThreads, D <= 128 ? 2 : 1) fwd_kernel(FusedParams p) {
     constexpr int BR = 128, BC = 64, KS = D / 16, MT = D / 32;
     constexpr int kTileBytes = BC * D * 2;
     constexpr int kStageBytes = 2 * kTileBytes;
@@ -266,6 +266,7 @@ hipError_t launch_fwd_fused(int d, const FusedParams& p, const int32_t* csr_ptr,
     switch (d) {
         case 64: return launch_fwd<64>(p, csr_ptr, csr_idx, stream);
         case 128: return launch_fwd<128>(p, csr_ptr, csr_idx, stream);
+        case 256: return launch_fwd<256>(p, csr_ptr, csr_idx, stream);
         default: return hipErrorInvalidValue;
     }
 }

@@ -1,4 +1,4 @@
-// Large-d path (d in {256, 512, 1024}): the regime where a d x d working set no longer fits the
+// Large-d path (d in {512, 1024}; the kernels also take 256): the regime where a d x d working set no longer fits the
 // per-CU LDS and register budget (the paper's small-cache case, M = o(d^2)).  It follows the
 // four-phase small-cache algorithm of App. C: square tiles with the contraction loop split
 // into chunks, and the n x n matrices f (here P) and p (here dS) written to memory between

@@ -37,10 +37,12 @@ CASES = [
     W("bf16_d128_sparse", 41, 1, 2, 1024, 128, "bf16", sparse=True, extra_frac=0.3),
     W("bf16_d128_sparse_ragged", 42, 1, 1, 1000, 128, "bf16", sparse=True, extra_frac=0.15),
     W("bf16_d64_sparse_causal", 43, 1, 2, 768, 64, "bf16", sparse=True, causal=True, extra_frac=0.5),
-    # large head dimension (small-cache regime)
+    # d = 256 (fused kernels, one wave per SIMD) and the large head dimensions (small-cache regime)
     W("bf16_d512", 51, 1, 2, 384, 512, "bf16"),
     W("bf16_d512_ragged_causal", 52, 1, 1, 200, 512, "bf16", causal=True),
     W("bf16_d256", 53, 1, 2, 256, 256, "bf16"),
+    W("bf16_d256_sparse_ragged", 60, 1, 2, 700, 256, "bf16", sparse=True, extra_frac=0.3),
+    W("bf16_d256_sparse_causal", 61, 1, 1, 512, 256, "bf16", sparse=True, causal=True, extra_frac=0.5),
     W("bf16_d512_causal_5blocks", 54, 1, 2, 640, 512, "bf16", causal=True, dO_std=0.1),
     W("bf16_d256_ragged_causal", 55, 2, 1, 333, 256, "bf16", causal=True),
     W("bf16_d1024", 58, 1, 1, 256, 1024, "bf16"),
@@ -104,7 +106,7 @@ def _run_all(w, inp, keep, causal):
     return [t.cpu() for t in (O, LSE, *g)]
 
 
-@pytest.mark.parametrize("d,dtype,block", [(128, "bf16", 128), (64, "bf16", 128), (32, "f32", 64)])
+@pytest.mark.parametrize("d,dtype,block", [(128, "bf16", 128), (64, "bf16", 128), (256, "bf16", 128), (32, "f32", 64)])
 def test_mask_logic_is_bit_exact(d, dtype, block):
     """An all-ones block mask must reproduce the dense result bit for bit, and a lower
     triangular block mask combined with the causal rule must reproduce causal bit for bit:
@@ -125,7 +127,7 @@ def test_mask_logic_is_bit_exact(d, dtype, block):
 
 
 @pytest.mark.parametrize("scale", [-0.11, 0.0, 0.35])
-@pytest.mark.parametrize("d,dtype", [(128, "bf16"), (64, "bf16"), (512, "bf16"), (48, "f32")])
+@pytest.mark.parametrize("d,dtype", [(128, "bf16"), (64, "bf16"), (256, "bf16"), (512, "bf16"), (48, "f32")])
 def test_unusual_scales(scale, d, dtype):
     """scale is any finite float: negative (the forward moves its sign into Q) and zero (uniform
     attention over the visible keys) must match the oracle like the usual 1/sqrt(d)."""
