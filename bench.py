@@ -81,7 +81,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--wgrad", action="store_true",
                     help="also time attn_bwd_wgrad (the paper's weight gradient) on the same shape and "
-                         "report it in an extra \"wgrad\" object (bf16, d <= 128, no block mask only)")
+                         "report it in an extra \"wgrad\" object (bf16, d <= 256, no block mask only)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy, so that HBM byte counters read in the "
                          "same profiler run can be scaled by a transfer of known size")
@@ -173,7 +173,7 @@ def main():
         # context for `frac`: what a register-only MFMA loop sustains on this GPU for random operands
         # (the clock under matrix load follows the power the data draws; `peak` assumes 2.4 GHz)
         out["mfma_ceiling_random_operands"] = mfma_ceiling(attn, torch, False, ms_target=40.0)
-    if args.wgrad and w.dtype == "bf16" and w.d in (64, 128) and not w.sparse:
+    if args.wgrad and w.dtype == "bf16" and w.d in (64, 128, 256) and not w.sparse:
         del grads, O, ws
         wi = synth.make_wgrad_inputs(w)
         A1, A2, A3, X, Y, G = (torch.from_numpy(wi[t]).to("cuda").to(dt) for t in ("A1", "A2", "A3", "X", "Y", "dO"))

@@ -109,7 +109,7 @@ attn_status attn_bwd_blocksparse(const attn_desc *desc, const attn_blockmask *ma
  * gradient of the loss with respect to the attention output (the paper's O - E).
  * The two projections, the forward, the dQ part of the backward and the product A_1^T dQ all run
  * on the device; queries, values, O and dQ pass through the workspace in bf16.
- * Supported: ATTN_BF16, d in {64, 128}, no block mask; anything else -> ATTN_ERR_UNSUPPORTED.
+ * Supported: ATTN_BF16, d in {64, 128, 256}, no block mask; anything else -> ATTN_ERR_UNSUPPORTED.
  * attn_wgrad_workspace_bytes returns 0 for an invalid or unsupported desc.
  */
 size_t attn_wgrad_workspace_bytes(const attn_desc *desc);

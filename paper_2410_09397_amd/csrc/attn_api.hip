@@ -196,11 +196,11 @@ attn_status bwd_impl(const attn_desc* desc, const attn_blockmask* mask, const vo
     return e == hipSuccess ? ATTN_OK : ATTN_ERR_DEVICE;
 }
 
-// Weight-gradient entry point: bf16, d in {64, 128}, contiguous [batch, heads, n, d] tensors.
+// Weight-gradient entry point: bf16, d in {64, 128, 256}, contiguous [batch, heads, n, d] tensors.
 attn_status wgrad_check(const attn_desc* d) {
     const attn_status st = check_desc(d);
     if (st != ATTN_OK) return st;
-    if (d->dtype != ATTN_BF16 || (d->d != 64 && d->d != 128)) return ATTN_ERR_UNSUPPORTED;
+    if (d->dtype != ATTN_BF16 || (d->d != 64 && d->d != 128 && d->d != 256)) return ATTN_ERR_UNSUPPORTED;
     if (!is_empty(d) && (d->stride_n != d->d || d->stride_h != (int64_t)d->n * d->d ||
                          d->stride_b != (int64_t)d->heads * d->n * d->d))
         return ATTN_ERR_UNSUPPORTED;

@@ -81,7 +81,7 @@ __global__ void __launch_bounds__(kThreads) proj_kernel(const __bf16* A, const _
 // streamed through LDS (two stages); both operands of every MFMA are transposed reads (the
 // contraction runs over the tiles' rows).  Waves form a 2 x 2 grid over the d x d output.
 template <int D>
-__global__ void __launch_bounds__(kThreads, 2) wgrad_partial_kernel(const __bf16* A1, const __bf16* dQ, float* part,
+__global__ void __launch_bounds__(kThreads, D <= 128 ? 2 : 1) wgrad_partial_kernel(const __bf16* A1, const __bf16* dQ, float* part,
                                                                     int n, int chunks) {
     constexpr int BR = 64, TW = D / 64;  // 32 x 32 output tiles per wave and dimension
     constexpr int kTileBytes = BR * D * 2, kStageBytes = 2 * kTileBytes;
@@ -230,6 +230,7 @@ hipError_t launch_wgrad_fused(int d, const WgradParams& p, hipStream_t stream) {
     switch (d) {
         case 64: return run<64>(p, stream);
         case 128: return run<128>(p, stream);
+        case 256: return run<256>(p, stream);
         default: return hipErrorInvalidValue;
     }
 }

@@ -37,7 +37,7 @@ def _composed_reference(inp, b, h, scale, causal):
     return A1.T @ dQ[0, 0]
 
 
-@pytest.mark.parametrize("n,d,heads", [(256, 64, 2), (320, 128, 2), (1100, 128, 1), (64, 64, 3)])
+@pytest.mark.parametrize("n,d,heads", [(256, 64, 2), (320, 128, 2), (1100, 128, 1), (64, 64, 3), (300, 256, 2)])
 def test_wgrad_matches_the_papers_algorithm(n, d, heads):
     w = synth.workload(2).small(batch=1, heads=heads, n=n, d=d)
     inp = synth.make_wgrad_inputs(w)
@@ -49,7 +49,7 @@ def test_wgrad_matches_the_papers_algorithm(n, d, heads):
         assert helpers.rel_err(g[0, h], ref) <= TOL
 
 
-@pytest.mark.parametrize("n,d,scale,causal", [(384, 128, 1.0, True), (200, 64, 0.7, False), (2112, 128, 1.3, True)])
+@pytest.mark.parametrize("n,d,scale,causal", [(384, 128, 1.0, True), (200, 64, 0.7, False), (2112, 128, 1.3, True), (1100, 256, 0.9, True)])
 def test_wgrad_with_scale_and_causal_mask(n, d, scale, causal):
     w = synth.workload(3).small(batch=2, heads=2, n=n, d=d)
     inp = synth.make_wgrad_inputs(w)
