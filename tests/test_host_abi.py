@@ -106,8 +106,8 @@ def test_wgrad_entry_point_validates_before_launch():
     assert call_wgrad(d, ptrs=(P, P, P, P, P, P + 4, P)) == attn.ATTN_ERR_INVALID_ARG
     assert call_wgrad(d, ws=None) == attn.ATTN_ERR_WORKSPACE
     assert call_wgrad(d, ws_bytes=need - 1) == attn.ATTN_ERR_WORKSPACE
-    for kw in (dict(dtype=attn.ATTN_F32), dict(d=256, stride_n=256, stride_h=128 * 256, stride_b=128 * 256),
-               dict(stride_n=128, stride_h=128 * 128, stride_b=128 * 128)):  # fp32, d > 128, padded rows
+    for kw in (dict(dtype=attn.ATTN_F32), dict(d=512, stride_n=512, stride_h=128 * 512, stride_b=128 * 512),
+               dict(stride_n=128, stride_h=128 * 128, stride_b=128 * 128)):  # fp32, d > 256, padded rows
         bad = desc(**kw)
         assert call_wgrad(bad) == attn.ATTN_ERR_UNSUPPORTED
         assert L.attn_wgrad_workspace_bytes(ctypes.byref(bad)) == 0
