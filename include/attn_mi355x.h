@@ -8,8 +8,8 @@
  *       s_ij = scale * <Q_i, K_j> over visible (i, j);  l_i = sum_j exp(s_ij);
  *       O_i = sum_j exp(s_ij) / l_i * V_j;              LSE_i = log l_i
  *   backward (App. B.4, definitions of q and p; Sec. 3.1, backward gradient; the tiling follows
- *             the large-cache phase-2 algorithm of App. D for d <= 128 and the four-phase
- *             small-cache algorithm of App. C for d > 128)
+ *             the large-cache phase-2 algorithm of App. D for d <= 256 and the four-phase
+ *             small-cache algorithm of App. C for d > 256)
  *       f_ij = exp(s_ij - LSE_i);  v_i = <dO_i, O_i>;  q_ij = <dO_i, V_j>;  p_ij = f_ij (q_ij - v_i)
  *       dV_j = sum_i f_ij dO_i;  dK_j = scale sum_i p_ij Q_i;  dQ_i = scale sum_j p_ij K_j
  * The paper has no scale and no mask; scale multiplies Q K^T, and a pair (i, j) is visible iff
@@ -75,13 +75,13 @@ typedef struct {
 } attn_blockmask;
 
 /* Bytes of device scratch that attn_fwd, attn_bwd and attn_bwd_blocksparse need for `desc`
- * (one figure that covers all three; 0 if desc or mask is invalid).  For d <= 128 it holds the
- * [batch, heads, n] row sums v; for d > 128 (App. C path) also the n x n matrices f and p of
+ * (one figure that covers all three; 0 if desc or mask is invalid).  For d <= 256 it holds the
+ * [batch, heads, n] row sums v; for d > 256 (App. C path) also the n x n matrices f and p of
  * every (batch, head) in bf16, with n rounded up to 256. */
 size_t attn_workspace_bytes(const attn_desc *desc, const attn_blockmask *mask /* nullable */);
 
 /* Forward: writes O [batch, heads, n, d] and LSE [batch, heads, n].  `mask` may be NULL.
- * `workspace` is read only when d > 128 and may be NULL otherwise. */
+ * `workspace` is read only when d > 256 and may be NULL otherwise. */
 attn_status attn_fwd(const attn_desc *desc, const attn_blockmask *mask, const void *Q,
                      const void *K, const void *V, void *O, float *LSE, void *workspace,
                      size_t workspace_bytes, void *stream);
