@@ -134,7 +134,8 @@ attn_status attn_blockmask_validate(int32_t block, int32_t nblk, int32_t n,
  *              (cycle counter against the 100 MHz constant-rate counter), valid after the stream
  *              has been synchronised
  *   flops      HOST double[1]: floating-point operations the launch executes
- * Errors: ATTN_ERR_INVALID_ARG (iters < 1, null pointers), ATTN_ERR_DEVICE.
+ * Errors: ATTN_ERR_INVALID_ARG (iters outside 1 .. 4 000 000, i.e. about a second of GPU time;
+ * null pointers), ATTN_ERR_DEVICE.
  */
 attn_status attn_mfma_ceiling(int32_t iters, int32_t zero_operands, float *clock_ghz, double *flops,
                               void *stream);

@@ -78,7 +78,7 @@ __global__ void __launch_bounds__(kThreads) mfma_ceiling_kernel(float* result, i
 extern "C" {
 
 attn_status attn_mfma_ceiling(int32_t iters, int32_t zero_operands, float* clock_ghz, double* flops, void* stream) {
-    if (iters < 1 || !clock_ghz || !flops) return ATTN_ERR_INVALID_ARG;
+    if (iters < 1 || iters > 4000000 || !clock_ghz || !flops) return ATTN_ERR_INVALID_ARG;  // <= about 1 s of GPU time
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess) return ATTN_ERR_DEVICE;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return ATTN_ERR_DEVICE;

@@ -162,3 +162,12 @@ def test_synthetic_inputs_are_reproducible_and_rounded():
     assert w5.extra_blocks == 13 and abs(w5.kept_fraction() - 1792 / 16384) < 1e-12
     assert abs(w5.bwd_flops() - 6.013e11) / 6.013e11 < 1e-3
     assert abs(synth.workload(3).bwd_flops() - 2.749e12) / 2.749e12 < 1e-3
+
+
+def test_mfma_ceiling_rejects_bad_arguments_before_launch():
+    L = attn.lib()
+    flops = ctypes.c_double(0.0)
+    assert L.attn_mfma_ceiling(0, 0, P, ctypes.byref(flops), None) == attn.ATTN_ERR_INVALID_ARG
+    assert L.attn_mfma_ceiling(5000000, 0, P, ctypes.byref(flops), None) == attn.ATTN_ERR_INVALID_ARG
+    assert L.attn_mfma_ceiling(100, 0, None, ctypes.byref(flops), None) == attn.ATTN_ERR_INVALID_ARG
+    assert L.attn_mfma_ceiling(100, 0, P, None, None) == attn.ATTN_ERR_INVALID_ARG
