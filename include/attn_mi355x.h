@@ -76,7 +76,8 @@ typedef struct {
 
 /* Bytes of device scratch that attn_fwd, attn_bwd and attn_bwd_blocksparse need for `desc`
  * (one figure that covers all three; 0 if desc or mask is invalid).  For d <= 256 it holds the
- * [batch, heads, n] row sums v; for d > 256 (App. C path) also the n x n matrices f and p of
+ * [batch, heads, n] row sums v (and, under a block mask, two lists of ceil(n / 128) block indices:
+ * the order in which the workgroups take the blocks); for d > 256 (App. C path) also the n x n matrices f and p of
  * every (batch, head) in bf16, with n rounded up to 256. */
 size_t attn_workspace_bytes(const attn_desc *desc, const attn_blockmask *mask /* nullable */);
 

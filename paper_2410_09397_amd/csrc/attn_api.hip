@@ -59,6 +59,8 @@ attn_status check_path(const attn_desc* d, const attn_blockmask* m) {
 }
 
 size_t delta_bytes(const attn_desc* d) { return round_up((size_t)d->batch * d->heads * d->n * sizeof(float), 256); }
+// two lists of 128-row block indices (query blocks, key blocks) for the masked fused backward
+size_t order_bytes(const attn_desc* d) { return round_up(2 * (((size_t)d->n + 127) / 128) * sizeof(int32_t), 256); }
 
 // Workspace layout of the large-d path.  Backward: [delta][P][dS]; forward: [stat_m][stat_l][P].
 size_t npad_of(const attn_desc* d) { return round_up((size_t)d->n, 256); }  // the product kernels' row block
@@ -152,7 +154,9 @@ attn_status bwd_impl(const attn_desc* desc, const attn_blockmask* mask, const vo
             p.LSE = LSE;
             p.delta = static_cast<float*>(workspace);
             e = attn::launch_bwd_fused(desc->d, p, mask ? mask->row_ptr : nullptr, mask ? mask->col_idx : nullptr,
-                                       mask ? mask->col_ptr : nullptr, mask ? mask->row_idx : nullptr, s);
+                                       mask ? mask->col_ptr : nullptr, mask ? mask->row_idx : nullptr, s, false,
+                                       mask ? reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + delta_bytes(desc))
+                                            : nullptr);
             break;
         }
         case Path::kLargeD: {
@@ -239,7 +243,7 @@ size_t attn_workspace_bytes(const attn_desc* desc, const attn_blockmask* mask) {
         const size_t fwd = 2 * stat_bytes(desc) + nn_bytes(desc);
         return bwd > fwd ? bwd : fwd;
     }
-    return delta_bytes(desc);
+    return delta_bytes(desc) + (mask && pick_path(desc, mask) == Path::kFused ? order_bytes(desc) : 0);
 }
 
 attn_status attn_fwd(const attn_desc* desc, const attn_blockmask* mask, const void* Q, const void* K,

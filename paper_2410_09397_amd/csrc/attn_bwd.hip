@@ -41,6 +41,22 @@ __global__ void __launch_bounds__(kThreads) delta_kernel(FusedParams p, int d) {
     if (r < rows && c == 0) p.delta[r] = acc;
 }
 
+// --------------------------------------------------------------------------- block order
+// order[r] = the block with the r-th longest list (ties: lower index first).  Workgroups are
+// dispatched in index order, so taking the long lists first keeps the tail of a launch short
+// when the lists of a block mask differ in length.  One thread per block, nblk^2 comparisons.
+__global__ void __launch_bounds__(kThreads) block_order_kernel(const int32_t* ptr, int nblk, int32_t* order) {
+    const int i = blockIdx.x * kThreads + threadIdx.x;
+    if (i >= nblk) return;
+    const int mine = ptr[i + 1] - ptr[i];
+    int rank = 0;
+    for (int k = 0; k < nblk; ++k) {
+        const int other = ptr[k + 1] - ptr[k];
+        rank += (other > mine || (other == mine && k < i)) ? 1 : 0;
+    }
+    order[rank] = i;
+}
+
 // ------------------------------------------------------------------------------- dK, dV
 // A workgroup owns 64 keys and streams 64-query tiles; per tile its 4 waves work in two phases:
 //   phase 1: wave (wk, wx) computes S^T and dP^T for key half wk and query half wx, with the
@@ -68,9 +84,15 @@ __global__ void __launch_bounds__(kThreads, D <= 128 ? 2 : 1) bwd_dkdv_kernel(Fu
     const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, l32 = lane & 31;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, uniform
     const int wk = w & 1, wx = w >> 1;
-    const int key_blocks = (p.n + BC - 1) / BC;
+    // with an order list the grid has both halves of every 128-key block (the last one may lie
+    // past n) and the blocks come longest list first
+    const int key_blocks = p.order ? 2 * ((p.n + 127) / 128) : (p.n + BC - 1) / BC;
     int bh, j;
     decode_block(blockIdx.x, key_blocks, p.batch * p.heads, bh, j);
+    if (p.order) {
+        j = 2 * p.order[j >> 1] + (j & 1);
+        if (j * BC >= p.n) return;
+    }
     const long base = (long)(bh / p.heads) * p.stride_b + (long)(bh % p.heads) * p.stride_h;
     const long ld = p.stride_n;
     const int j0 = j * BC;
@@ -345,7 +367,8 @@ __global__ void __launch_bounds__(kThreads, QT == 1 && D <= 128 ? 2 : 1) bwd_dq_
     const int q_blocks = (p.n + BR - 1) / BR;
     int bh, blk;
     decode_block(blockIdx.x, q_blocks, p.batch * p.heads, bh, blk);
-    const int ib = p.causal ? q_blocks - 1 - blk : blk;  // causal: longest rows first
+    // longest rows first: under the causal rule the last blocks, under a block mask by the order list
+    const int ib = p.order ? p.order[blk] : (p.causal ? q_blocks - 1 - blk : blk);
     const long base = (long)(bh / p.heads) * p.stride_b + (long)(bh % p.heads) * p.stride_h;
     const long ld = p.stride_n;
     const int i0 = ib * BR;
@@ -558,7 +581,8 @@ void launch_delta(const FusedParams& p, int d, hipStream_t stream) {
 
 template <int D>
 static hipError_t launch_bwd(const FusedParams& p, const int32_t* csr_ptr, const int32_t* csr_idx,
-                             const int32_t* csc_ptr, const int32_t* csc_idx, hipStream_t stream, bool dq_only) {
+                             const int32_t* csc_ptr, const int32_t* csc_idx, hipStream_t stream, bool dq_only,
+                             int32_t* order_scratch) {
     const int bh = p.batch * p.heads;
 
     constexpr int kv_lds = 2 * (2 * 64 * D * 2) + 2 * 64 * 64 * 2;  // two stages of Q, dO; P and dS
@@ -574,9 +598,19 @@ static hipError_t launch_bwd(const FusedParams& p, const int32_t* csr_ptr, const
         configured = true;
     }
     const int blocks128 = (p.n + 127) / 128;
+    int32_t* order_q = nullptr;
+    int32_t* order_k = nullptr;
+    if (order_scratch && csr_ptr && csc_ptr) {
+        order_q = order_scratch;
+        order_k = order_scratch + blocks128;
+        const dim3 og((unsigned)((blocks128 + kThreads - 1) / kThreads));
+        hipLaunchKernelGGL(block_order_kernel, og, dim3(kThreads), 0, stream, csr_ptr, blocks128, order_q);
+        if (!dq_only) hipLaunchKernelGGL(block_order_kernel, og, dim3(kThreads), 0, stream, csc_ptr, blocks128, order_k);
+    }
     FusedParams pq = p;
     pq.list_ptr = csr_ptr;
     pq.list_idx = csr_idx;
+    pq.order = order_q;
     // One query tile per wave and two workgroups per CU.  (QT = 2, i.e. one wave per SIMD with every
     // LDS fragment feeding two MFMAs, halves the LDS traffic but measured 20 % slower at d = 128:
     // with a single wave per SIMD the softmax arithmetic no longer overlaps another wave's MFMAs.)
@@ -585,16 +619,19 @@ static hipError_t launch_bwd(const FusedParams& p, const int32_t* csr_ptr, const
     FusedParams pk = p;
     pk.list_ptr = csc_ptr;
     pk.list_idx = csc_idx;
-    hipLaunchKernelGGL(bwd_dkdv_kernel<D>, dim3((unsigned)((p.n + 63) / 64 * bh)), dim3(kThreads), kv_lds, stream, pk);
+    pk.order = order_k;
+    const int key_blocks = order_k ? 2 * blocks128 : (p.n + 63) / 64;
+    hipLaunchKernelGGL(bwd_dkdv_kernel<D>, dim3((unsigned)(key_blocks * bh)), dim3(kThreads), kv_lds, stream, pk);
     return hipGetLastError();
 }
 
 hipError_t launch_bwd_fused(int d, const FusedParams& p, const int32_t* csr_ptr, const int32_t* csr_idx,
-                            const int32_t* csc_ptr, const int32_t* csc_idx, hipStream_t stream, bool dq_only) {
+                            const int32_t* csc_ptr, const int32_t* csc_idx, hipStream_t stream, bool dq_only,
+                            int32_t* order_scratch) {
     switch (d) {
-        case 64: return launch_bwd<64>(p, csr_ptr, csr_idx, csc_ptr, csc_idx, stream, dq_only);
-        case 128: return launch_bwd<128>(p, csr_ptr, csr_idx, csc_ptr, csc_idx, stream, dq_only);
-        case 256: return launch_bwd<256>(p, csr_ptr, csr_idx, csc_ptr, csc_idx, stream, dq_only);
+        case 64: return launch_bwd<64>(p, csr_ptr, csr_idx, csc_ptr, csc_idx, stream, dq_only, order_scratch);
+        case 128: return launch_bwd<128>(p, csr_ptr, csr_idx, csc_ptr, csc_idx, stream, dq_only, order_scratch);
+        case 256: return launch_bwd<256>(p, csr_ptr, csr_idx, csc_ptr, csc_idx, stream, dq_only, order_scratch);
         default: return hipErrorInvalidValue;
     }
 }

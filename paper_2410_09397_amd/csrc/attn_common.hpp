@@ -331,6 +331,9 @@ struct FusedParams {
     // block-sparse lists (nullptr = dense): ptr/idx give, per 128-row block of the resident
     // operand, the 128-row blocks of the streamed operand that are visible, ascending.
     const int32_t *list_ptr, *list_idx;
+    // under a block mask, optionally: the 128-row blocks of the resident operand in the order the
+    // workgroups take them (longest list first), nullptr = ascending
+    const int32_t* order;
 };
 
 }  // namespace attn

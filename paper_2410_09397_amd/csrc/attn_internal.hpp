@@ -10,9 +10,11 @@ namespace attn {
 hipError_t launch_fwd_fused(int d, const FusedParams& p, const int32_t* csr_ptr, const int32_t* csr_idx,
                             hipStream_t stream);
 // dq_only: run the query-owner kernel alone (dQ and delta), for callers that need neither dK nor dV.
+// order_scratch: under a block mask, 2 * ceil(n / 128) int32 of device scratch for the order in
+// which the workgroups take the blocks (longest list first), or nullptr (ascending order).
 hipError_t launch_bwd_fused(int d, const FusedParams& p, const int32_t* csr_ptr, const int32_t* csr_idx,
                             const int32_t* csc_ptr, const int32_t* csc_idx, hipStream_t stream,
-                            bool dq_only = false);
+                            bool dq_only = false, int32_t* order_scratch = nullptr);
 
 // delta[b, h, i] = sum_k dO_ik O_ik for bf16 tensors (p.O, p.dO, p.delta), any d % 8 == 0.
 void launch_delta(const FusedParams& p, int d, hipStream_t stream);
