@@ -356,7 +356,7 @@ __global__ void __launch_bounds__(kThreads, D <= 128 ? 2 : 1) bwd_dkdv_kernel(Fu
 //   dS^T = P^T (dP^T - delta)                        per-lane scalars lse2, delta
 //   dQ_w^T += K_T^T dS^T                             K^T from transposed LDS reads
 template <int D, int QT>
-__global__ void __launch_bounds__(kThreads, QT == 1 && D <= 128 ? 2 : 1) bwd_dq_kernel(FusedParams p) {
+__global__ void __launch_bounds__(kThreads, D == 64 ? 4 : (QT == 1 && D <= 128 ? 2 : 1)) bwd_dq_kernel(FusedParams p) {
     constexpr int BR = 128 * QT, BC = 64, KS = D / 16, MT = D / 32;
     constexpr int kTileBytes = BC * D * 2;
     constexpr int kStageBytes = 2 * kTileBytes;
