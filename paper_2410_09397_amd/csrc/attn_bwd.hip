@@ -70,9 +70,9 @@ __global__ void __launch_bounds__(kThreads) block_order_kernel(const int32_t* pt
 // round trip for P and dS) needs more than 256 registers per lane at d = 128, i.e. one wave per
 // SIMD; that variant was measured at 60 % of this one's speed at d = 128 and 91 % at d = 64.
 // Wave priorities per phase: the two waves that share a SIMD compete for one matrix pipe and
-// fall into step; ranking phase 1 above the exponentials above phase 2 lets one of them run ahead
-// (measured: 3-4 % faster).
-constexpr int kPrioPhase1 = 3, kPrioSoftmax = 1, kPrioPhase2 = 0;
+// fall into step; ranking phase 1 above phase 2 above the exponentials lets one of them run ahead
+// (measured: 2 % faster than without priorities, 3 % faster than with the exponentials in the middle).
+constexpr int kPrioPhase1 = 3, kPrioSoftmax = 0, kPrioPhase2 = 1;
 template <int D>
 __global__ void __launch_bounds__(kThreads, D <= 128 ? 2 : 1) bwd_dkdv_kernel(FusedParams p) {
     constexpr int BR = 64, BC = 64, KS = D / 16, MT = D / 32;
