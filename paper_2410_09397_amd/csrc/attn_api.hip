@@ -59,8 +59,8 @@ attn_status check_path(const attn_desc* d, const attn_blockmask* m) {
 }
 
 size_t delta_bytes(const attn_desc* d) { return round_up((size_t)d->batch * d->heads * d->n * sizeof(float), 256); }
-// two lists of 128-row block indices (query blocks, key blocks) for the masked fused backward
-size_t order_bytes(const attn_desc* d) { return round_up(2 * (((size_t)d->n + 127) / 128) * sizeof(int32_t), 256); }
+// two lists of 128-row block indices (query blocks, key blocks) and one of list lengths for the masked fused backward
+size_t order_bytes(const attn_desc* d) { return round_up(3 * (((size_t)d->n + 127) / 128) * sizeof(int32_t), 256); }
 
 // Workspace layout of the large-d path.  Backward: [delta][P][dS]; forward: [stat_m][stat_l][P].
 size_t npad_of(const attn_desc* d) { return round_up((size_t)d->n, 256); }  // the product kernels' row block

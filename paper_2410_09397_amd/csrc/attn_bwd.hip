@@ -44,14 +44,29 @@ __global__ void __launch_bounds__(kThreads) delta_kernel(FusedParams p, int d) {
 // --------------------------------------------------------------------------- block order
 // order[r] = the block with the r-th longest list (ties: lower index first).  Workgroups are
 // dispatched in index order, so taking the long lists first keeps the tail of a launch short
-// when the lists of a block mask differ in length.  One thread per block, nblk^2 comparisons.
-__global__ void __launch_bounds__(kThreads) block_order_kernel(const int32_t* ptr, int nblk, int32_t* order) {
+// when the lists of a block mask differ in length, and workgroups that run at the same time walk
+// through the streamed blocks together (their re-reads then hit in L2).  Two steps: the list
+// lengths that count (entries the causal rule removes do not), then one thread per block ranks
+// its length against all others (nblk^2 comparisons).
+__global__ void __launch_bounds__(kThreads) block_len_kernel(const int32_t* ptr, const int32_t* idx, int nblk,
+                                                            int causal, int column_lists, int32_t* len) {
     const int i = blockIdx.x * kThreads + threadIdx.x;
     if (i >= nblk) return;
-    const int mine = ptr[i + 1] - ptr[i];
+    const int first = ptr[i];
+    int count = ptr[i + 1] - first;
+    if (causal) {
+        if (column_lists) count -= causal_col_skip(idx, first, count, i);
+        else count = causal_row_entries(idx, first, count, i);
+    }
+    len[i] = count;
+}
+__global__ void __launch_bounds__(kThreads) block_order_kernel(const int32_t* len, int nblk, int32_t* order) {
+    const int i = blockIdx.x * kThreads + threadIdx.x;
+    if (i >= nblk) return;
+    const int mine = len[i];
     int rank = 0;
     for (int k = 0; k < nblk; ++k) {
-        const int other = ptr[k + 1] - ptr[k];
+        const int other = len[k];
         rank += (other > mine || (other == mine && k < i)) ? 1 : 0;
     }
     order[rank] = i;
@@ -102,7 +117,13 @@ __global__ void __launch_bounds__(kThreads, D <= 128 ? 2 : 1) bwd_dkdv_kernel(Fu
     int n_it, t0 = 0, lp0 = 0;
     if (p.list_ptr) {
         lp0 = p.list_ptr[j0 / 128];
-        n_it = (p.list_ptr[j0 / 128 + 1] - lp0) * (128 / BR);
+        int entries = p.list_ptr[j0 / 128 + 1] - lp0;
+        if (p.causal) {
+            const int skip = causal_col_skip(p.list_idx, lp0, entries, j0 / 128);
+            lp0 += skip;
+            entries -= skip;
+        }
+        n_it = entries * (128 / BR);
     } else {
         t0 = p.causal ? j0 / BR : 0;
         n_it = (p.n + BR - 1) / BR - t0;
@@ -377,7 +398,9 @@ __global__ void __launch_bounds__(kThreads, D == 64 ? 4 : (QT == 1 && D <= 128 ?
     int n_it, lp0 = 0;
     if (p.list_ptr) {  // block lists are per 128 queries: only with QT == 1
         lp0 = p.list_ptr[ib];
-        n_it = (p.list_ptr[ib + 1] - lp0) * (128 / BC);
+        int entries = p.list_ptr[ib + 1] - lp0;
+        if (p.causal) entries = causal_row_entries(p.list_idx, lp0, entries, ib);
+        n_it = entries * (128 / BC);
     } else {
         const int k_end = p.causal ? min(p.n, i0 + BR) : p.n;
         n_it = (k_end + BC - 1) / BC;
@@ -603,9 +626,14 @@ static hipError_t launch_bwd(const FusedParams& p, const int32_t* csr_ptr, const
     if (order_scratch && csr_ptr && csc_ptr) {
         order_q = order_scratch;
         order_k = order_scratch + blocks128;
+        int32_t* len = order_scratch + 2 * blocks128;
         const dim3 og((unsigned)((blocks128 + kThreads - 1) / kThreads));
-        hipLaunchKernelGGL(block_order_kernel, og, dim3(kThreads), 0, stream, csr_ptr, blocks128, order_q);
-        if (!dq_only) hipLaunchKernelGGL(block_order_kernel, og, dim3(kThreads), 0, stream, csc_ptr, blocks128, order_k);
+        hipLaunchKernelGGL(block_len_kernel, og, dim3(kThreads), 0, stream, csr_ptr, csr_idx, blocks128, p.causal, 0, len);
+        hipLaunchKernelGGL(block_order_kernel, og, dim3(kThreads), 0, stream, len, blocks128, order_q);
+        if (!dq_only) {
+            hipLaunchKernelGGL(block_len_kernel, og, dim3(kThreads), 0, stream, csc_ptr, csc_idx, blocks128, p.causal, 1, len);
+            hipLaunchKernelGGL(block_order_kernel, og, dim3(kThreads), 0, stream, len, blocks128, order_k);
+        }
     }
     FusedParams pq = p;
     pq.list_ptr = csr_ptr;

@@ -303,6 +303,20 @@ __device__ __forceinline__ int tile_start_row(const int32_t* list_idx, int lp0, 
     return (t0 + it) * TILE;
 }
 
+// Block lists under the causal rule.  The row list of query block b (ascending key blocks) only
+// needs the entries <= b, the column list of key block b (ascending query blocks) only the entries
+// >= b: everything else is invisible, and a tile that is not in the list is neither copied nor
+// waited for.  All values are uniform (scalar loads).
+__device__ __forceinline__ int causal_row_entries(const int32_t* idx, int first, int count, int b) {
+    while (count > 0 && idx[first + count - 1] > b) --count;
+    return count;
+}
+__device__ __forceinline__ int causal_col_skip(const int32_t* idx, int first, int count, int b) {
+    int skip = 0;
+    while (skip < count && idx[first + skip] < b) ++skip;
+    return skip;
+}
+
 // Head and tile decoding shared by the kernels.  Workgroups are handed to the 8 XCDs round
 // robin by linear id, so ids congruent mod 8 share an L2: all tiles of one (batch, head) are
 // given to one XCD when the head count allows it.

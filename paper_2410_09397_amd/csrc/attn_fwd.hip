@@ -37,7 +37,9 @@ __global__ void __launch_bounds__(kThreads, D == 64 ? 4 : (D <= 128 ? 2 : 1)) fw
     int n_it, lp0 = 0;
     if (p.list_ptr) {
         lp0 = p.list_ptr[ib];
-        n_it = (p.list_ptr[ib + 1] - lp0) * (128 / BC);
+        int entries = p.list_ptr[ib + 1] - lp0;
+        if (p.causal) entries = causal_row_entries(p.list_idx, lp0, entries, ib);
+        n_it = entries * (128 / BC);
     } else {
         const int k_end = p.causal ? min(p.n, i0 + BR) : p.n;
         n_it = (k_end + BC - 1) / BC;

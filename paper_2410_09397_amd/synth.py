@@ -46,7 +46,8 @@ class Workload:
         """Fraction of the n x n score matrix counted as visible when quoting FLOPs
         (causal is counted as one half; the exact share is (n + 1) / 2n)."""
         if self.sparse:
-            return (1 + self.extra_blocks) / self.nblk
+            # with the causal rule on top: half of the diagonal block and, in expectation, half of the others
+            return (1 + self.extra_blocks) / self.nblk * (0.5 if self.causal else 1.0)
         if self.causal:
             return 0.5
         return 1.0
