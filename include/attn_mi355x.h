@@ -61,17 +61,23 @@ typedef struct {
 } attn_desc;
 
 /*
- * Block mask shared by all (batch, head) pairs: an nblk x nblk pattern of kept blocks, with
- * nblk = ceil(n / block), in both compressed orientations (DEVICE int32 arrays, caller owned):
+ * Block mask: an nblk x nblk pattern of kept blocks, nblk = ceil(n / block), in both compressed
+ * orientations (DEVICE int32 arrays, caller owned):
  *   row_ptr[nblk+1], col_idx[nnz]: key blocks kept for each query-block row, ascending;
  *   col_ptr[nblk+1], row_idx[nnz]: query blocks kept for each key-block column, ascending.
  * The two must describe the same set; attn_blockmask_validate checks host copies.
+ * nmasks == 0 or 1: one pattern shared by all (batch, head) pairs.  nmasks == batch * heads: one
+ * pattern per pair, mask m = b * heads + h; the arrays are the concatenations of the per-mask
+ * arrays, row_ptr and col_ptr with nblk + 1 entries per mask that index the concatenated col_idx
+ * and row_idx directly (entry 0 of mask m equals entry nblk of mask m - 1; mask 0 starts at 0).
+ * (The paper's sparse bound, Thm 4.5, only counts non-zero entries: it covers both.)
  */
 typedef struct {
     int32_t block;
     int32_t nblk;
     const int32_t *row_ptr, *col_idx;
     const int32_t *col_ptr, *row_idx;
+    int32_t nmasks;
 } attn_blockmask;
 
 /* Bytes of device scratch that attn_fwd, attn_bwd and attn_bwd_blocksparse need for `desc`
@@ -118,9 +124,10 @@ attn_status attn_bwd_wgrad(const attn_desc *desc, const void *A1, const void *A2
                            const void *X, const void *Y, const void *dO, float *g,
                            void *workspace, size_t workspace_bytes, void *stream);
 
-/* Checks HOST copies of a block mask: monotone pointers, strictly ascending in-range indices,
- * nblk == ceil(n / block), and that the two orientations hold the same pairs. */
-attn_status attn_blockmask_validate(int32_t block, int32_t nblk, int32_t n,
+/* Checks HOST copies of a block mask (nmasks patterns, 0 counts as 1): monotone pointers that
+ * continue from one pattern to the next, strictly ascending in-range indices,
+ * nblk == ceil(n / block), and that the two orientations of every pattern hold the same pairs. */
+attn_status attn_blockmask_validate(int32_t block, int32_t nblk, int32_t n, int32_t nmasks,
                                     const int32_t *row_ptr, const int32_t *col_idx,
                                     const int32_t *col_ptr, const int32_t *row_idx);
 

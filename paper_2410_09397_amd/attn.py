@@ -31,7 +31,7 @@ class attn_desc(ctypes.Structure):
 class attn_blockmask(ctypes.Structure):
     _fields_ = [("block", ctypes.c_int32), ("nblk", ctypes.c_int32),
                 ("row_ptr", ctypes.c_void_p), ("col_idx", ctypes.c_void_p),
-                ("col_ptr", ctypes.c_void_p), ("row_idx", ctypes.c_void_p)]
+                ("col_ptr", ctypes.c_void_p), ("row_idx", ctypes.c_void_p), ("nmasks", ctypes.c_int32)]
 
 
 class AttnError(RuntimeError):
@@ -65,7 +65,7 @@ def lib():
         L.attn_bwd_wgrad.restype = ctypes.c_int
         L.attn_bwd_wgrad.argtypes = [dp] + [vp] * 7 + [vp, ctypes.c_size_t, vp]
         L.attn_blockmask_validate.restype = ctypes.c_int
-        L.attn_blockmask_validate.argtypes = [ctypes.c_int32] * 3 + [i32p] * 4
+        L.attn_blockmask_validate.argtypes = [ctypes.c_int32] * 4 + [i32p] * 4
         L.attn_mfma_ceiling.restype = ctypes.c_int
         L.attn_mfma_ceiling.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.attn_status_str.restype = ctypes.c_char_p
@@ -79,40 +79,53 @@ def status_str(status):
 
 
 def csr_csc_from_dense(keep):
-    """Host int32 arrays (row_ptr, col_idx, col_ptr, row_idx) of an [nblk, nblk] 0/1 matrix."""
+    """Host int32 arrays (row_ptr, col_idx, col_ptr, row_idx) of an [nblk, nblk] 0/1 matrix, or of a stack
+    [nmasks, nblk, nblk] of them in the concatenated form of include/attn_mi355x.h (pointer arrays of
+    nblk + 1 entries per mask that index the concatenated index arrays)."""
     keep = np.asarray(keep) != 0
-    nblk = keep.shape[0]
-    row_ptr = np.zeros(nblk + 1, np.int32)
-    row_ptr[1:] = np.cumsum(keep.sum(1))
-    col_idx = np.nonzero(keep)[1].astype(np.int32)
-    col_ptr = np.zeros(nblk + 1, np.int32)
-    col_ptr[1:] = np.cumsum(keep.sum(0))
-    row_idx = np.nonzero(keep.T)[1].astype(np.int32)
-    return row_ptr, col_idx, col_ptr, row_idx
+    stack = keep[None] if keep.ndim == 2 else keep
+    nblk = stack.shape[1]
+    row_ptr, col_idx, col_ptr, row_idx = [], [], [], []
+    start = 0
+    for k in stack:
+        rp = np.zeros(nblk + 1, np.int64)
+        rp[1:] = np.cumsum(k.sum(1))
+        cp = np.zeros(nblk + 1, np.int64)
+        cp[1:] = np.cumsum(k.sum(0))
+        row_ptr.append(rp + start)
+        col_ptr.append(cp + start)
+        col_idx.append(np.nonzero(k)[1])
+        row_idx.append(np.nonzero(k.T)[1])
+        start += int(rp[-1])
+    cat = lambda parts: np.concatenate(parts).astype(np.int32)
+    return cat(row_ptr), cat(col_idx), cat(col_ptr), cat(row_idx)
 
 
-def attn_blockmask_validate(block, nblk, n, row_ptr, col_idx, col_ptr, row_idx):
+def attn_blockmask_validate(block, nblk, n, row_ptr, col_idx, col_ptr, row_idx, nmasks=1):
     """Status code of the host-side structural check of a block mask (numpy int32 arrays)."""
     i32p = ctypes.POINTER(ctypes.c_int32)
     arrs = [np.ascontiguousarray(a, dtype=np.int32) if a is not None else None
             for a in (row_ptr, col_idx, col_ptr, row_idx)]
     ptrs = [a.ctypes.data_as(i32p) if a is not None else None for a in arrs]
-    return lib().attn_blockmask_validate(int(block), int(nblk), int(n), *ptrs)
+    return lib().attn_blockmask_validate(int(block), int(nblk), int(n), int(nmasks), *ptrs)
 
 
 class BlockMask:
-    """Device copies of a block mask in both compressed orientations."""
+    """Device copies of a block mask in both compressed orientations.  `keep` is [nblk, nblk] (one
+    pattern for all batches and heads) or [batch * heads, nblk, nblk] (one per pair)."""
 
     def __init__(self, keep, block, n, device="cuda"):
         import torch
+        keep = np.asarray(keep)
         self.block, self.n = int(block), int(n)
-        self.nblk = int(np.asarray(keep).shape[0])
+        self.nblk = int(keep.shape[-1])
+        self.nmasks = 1 if keep.ndim == 2 else int(keep.shape[0])
         self.host = csr_csc_from_dense(keep)
-        st = attn_blockmask_validate(self.block, self.nblk, self.n, *self.host)
+        st = attn_blockmask_validate(self.block, self.nblk, self.n, *self.host, nmasks=self.nmasks)
         if st != ATTN_OK:
             raise AttnError(st, "attn_blockmask_validate")
         self.dev = [torch.from_numpy(a).to(device) for a in self.host]
-        self.c = attn_blockmask(self.block, self.nblk, *[t.data_ptr() for t in self.dev])
+        self.c = attn_blockmask(self.block, self.nblk, *[t.data_ptr() for t in self.dev], self.nmasks)
 
 
 def _desc(x, scale, causal):

@@ -1,5 +1,6 @@
 // C ABI of libattn_mi355x.so: host-side validation and dispatch.  No device memory is
 // allocated here and nothing is launched before every argument has been checked.
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <vector>
@@ -40,6 +41,7 @@ attn_status check_mask(const attn_desc* d, const attn_blockmask* m) {
     if (m->block < 1 || m->nblk < 0) return ATTN_ERR_INVALID_ARG;
     if ((long)m->nblk != ((long)d->n + m->block - 1) / m->block) return ATTN_ERR_INVALID_ARG;
     if (!m->row_ptr || !m->col_idx || !m->col_ptr || !m->row_idx) return ATTN_ERR_INVALID_ARG;
+    if (m->nmasks != 0 && m->nmasks != 1 && (long)m->nmasks != (long)d->batch * d->heads) return ATTN_ERR_INVALID_ARG;
     return ATTN_OK;
 }
 
@@ -60,7 +62,10 @@ attn_status check_path(const attn_desc* d, const attn_blockmask* m) {
 
 size_t delta_bytes(const attn_desc* d) { return round_up((size_t)d->batch * d->heads * d->n * sizeof(float), 256); }
 // two lists of 128-row block indices (query blocks, key blocks) and one of list lengths for the masked fused backward
-size_t order_bytes(const attn_desc* d) { return round_up(3 * (((size_t)d->n + 127) / 128) * sizeof(int32_t), 256); }
+int mask_count(const attn_blockmask* m) { return m && m->nmasks > 1 ? m->nmasks : 1; }
+size_t order_bytes(const attn_desc* d, const attn_blockmask* m) {
+    return round_up((size_t)mask_count(m) * 3 * (((size_t)d->n + 127) / 128) * sizeof(int32_t), 256);
+}
 
 // Workspace layout of the large-d path.  Backward: [delta][P][dS]; forward: [stat_m][stat_l][P].
 size_t npad_of(const attn_desc* d) { return round_up((size_t)d->n, 256); }  // the product kernels' row block
@@ -118,6 +123,7 @@ GenericParams generic_params(const attn_desc* d, const attn_blockmask* m) {
         p.csc_ptr = m->col_ptr;
         p.csc_idx = m->row_idx;
         p.block = m->block;
+        p.mask_stride = m->nmasks > 1 ? m->nblk + 1 : 0;
     }
     return p;
 }
@@ -153,6 +159,7 @@ attn_status bwd_impl(const attn_desc* desc, const attn_blockmask* mask, const vo
             p.dV = static_cast<__bf16*>(dV);
             p.LSE = LSE;
             p.delta = static_cast<float*>(workspace);
+            p.list_stride = mask && mask->nmasks > 1 ? mask->nblk + 1 : 0;
             e = attn::launch_bwd_fused(desc->d, p, mask ? mask->row_ptr : nullptr, mask ? mask->col_idx : nullptr,
                                        mask ? mask->col_ptr : nullptr, mask ? mask->row_idx : nullptr, s, false,
                                        mask ? reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + delta_bytes(desc))
@@ -243,7 +250,7 @@ size_t attn_workspace_bytes(const attn_desc* desc, const attn_blockmask* mask) {
         const size_t fwd = 2 * stat_bytes(desc) + nn_bytes(desc);
         return bwd > fwd ? bwd : fwd;
     }
-    return delta_bytes(desc) + (mask && pick_path(desc, mask) == Path::kFused ? order_bytes(desc) : 0);
+    return delta_bytes(desc) + (mask && pick_path(desc, mask) == Path::kFused ? order_bytes(desc, mask) : 0);
 }
 
 attn_status attn_fwd(const attn_desc* desc, const attn_blockmask* mask, const void* Q, const void* K,
@@ -272,6 +279,7 @@ attn_status attn_fwd(const attn_desc* desc, const attn_blockmask* mask, const vo
             p.V = static_cast<const __bf16*>(V);
             p.Oout = static_cast<__bf16*>(O);
             p.LSEout = LSE;
+            p.list_stride = mask && mask->nmasks > 1 ? mask->nblk + 1 : 0;
             e = attn::launch_fwd_fused(desc->d, p, mask ? mask->row_ptr : nullptr, mask ? mask->col_idx : nullptr, s);
             break;
         }
@@ -368,32 +376,40 @@ attn_status attn_bwd_wgrad(const attn_desc* desc, const void* A1, const void* A2
     return e == hipSuccess ? ATTN_OK : ATTN_ERR_DEVICE;
 }
 
-attn_status attn_blockmask_validate(int32_t block, int32_t nblk, int32_t n, const int32_t* row_ptr,
+attn_status attn_blockmask_validate(int32_t block, int32_t nblk, int32_t n, int32_t nmasks, const int32_t* row_ptr,
                                     const int32_t* col_idx, const int32_t* col_ptr, const int32_t* row_idx) {
-    if (block < 1 || nblk < 0 || n < 0) return ATTN_ERR_INVALID_ARG;
+    if (block < 1 || nblk < 0 || n < 0 || nmasks < 0) return ATTN_ERR_INVALID_ARG;
     if ((long)nblk != ((long)n + block - 1) / block) return ATTN_ERR_INVALID_ARG;
     if (!row_ptr || !col_ptr || (nblk > 0 && (!col_idx || !row_idx))) return ATTN_ERR_INVALID_ARG;
     if (row_ptr[0] != 0 || col_ptr[0] != 0) return ATTN_ERR_INVALID_ARG;
-    for (int a = 0; a < nblk; ++a) {
-        if (row_ptr[a + 1] < row_ptr[a] || col_ptr[a + 1] < col_ptr[a]) return ATTN_ERR_INVALID_ARG;
-        if (row_ptr[a + 1] - row_ptr[a] > nblk || col_ptr[a + 1] - col_ptr[a] > nblk) return ATTN_ERR_INVALID_ARG;
+    std::vector<unsigned char> keep((size_t)nblk * nblk);
+    const int masks = nmasks > 1 ? nmasks : 1;
+    for (int m = 0; m < masks; ++m) {
+        const int32_t* rp = row_ptr + (size_t)m * (nblk + 1);
+        const int32_t* cp = col_ptr + (size_t)m * (nblk + 1);
+        // the lists of mask m continue where those of mask m - 1 end
+        if (m > 0 && (rp[0] != rp[-1] || cp[0] != cp[-1])) return ATTN_ERR_INVALID_ARG;
+        for (int a = 0; a < nblk; ++a) {
+            if (rp[a + 1] < rp[a] || cp[a + 1] < cp[a]) return ATTN_ERR_INVALID_ARG;
+            if (rp[a + 1] - rp[a] > nblk || cp[a + 1] - cp[a] > nblk) return ATTN_ERR_INVALID_ARG;
+        }
+        if (rp[nblk] != cp[nblk] || rp[0] != cp[0]) return ATTN_ERR_INVALID_ARG;
+        std::fill(keep.begin(), keep.end(), 0);
+        for (int i = 0; i < nblk; ++i)
+            for (int a = rp[i]; a < rp[i + 1]; ++a) {
+                const int j = col_idx[a];
+                if (j < 0 || j >= nblk) return ATTN_ERR_INVALID_ARG;
+                if (a > rp[i] && col_idx[a - 1] >= j) return ATTN_ERR_INVALID_ARG;
+                keep[(size_t)i * nblk + j] = 1;
+            }
+        for (int j = 0; j < nblk; ++j)
+            for (int a = cp[j]; a < cp[j + 1]; ++a) {
+                const int i = row_idx[a];
+                if (i < 0 || i >= nblk) return ATTN_ERR_INVALID_ARG;
+                if (a > cp[j] && row_idx[a - 1] >= i) return ATTN_ERR_INVALID_ARG;
+                if (!keep[(size_t)i * nblk + j]) return ATTN_ERR_INVALID_ARG;
+            }
     }
-    if (row_ptr[nblk] != col_ptr[nblk]) return ATTN_ERR_INVALID_ARG;
-    std::vector<unsigned char> keep((size_t)nblk * nblk, 0);
-    for (int i = 0; i < nblk; ++i)
-        for (int a = row_ptr[i]; a < row_ptr[i + 1]; ++a) {
-            const int j = col_idx[a];
-            if (j < 0 || j >= nblk) return ATTN_ERR_INVALID_ARG;
-            if (a > row_ptr[i] && col_idx[a - 1] >= j) return ATTN_ERR_INVALID_ARG;
-            keep[(size_t)i * nblk + j] = 1;
-        }
-    for (int j = 0; j < nblk; ++j)
-        for (int a = col_ptr[j]; a < col_ptr[j + 1]; ++a) {
-            const int i = row_idx[a];
-            if (i < 0 || i >= nblk) return ATTN_ERR_INVALID_ARG;
-            if (a > col_ptr[j] && row_idx[a - 1] >= i) return ATTN_ERR_INVALID_ARG;
-            if (!keep[(size_t)i * nblk + j]) return ATTN_ERR_INVALID_ARG;
-        }
     return ATTN_OK;
 }
 

@@ -48,10 +48,12 @@ __global__ void __launch_bounds__(kThreads) delta_kernel(FusedParams p, int d) {
 // through the streamed blocks together (their re-reads then hit in L2).  Two steps: the list
 // lengths that count (entries the causal rule removes do not), then one thread per block ranks
 // its length against all others (nblk^2 comparisons).
-__global__ void __launch_bounds__(kThreads) block_len_kernel(const int32_t* ptr, const int32_t* idx, int nblk,
-                                                            int causal, int column_lists, int32_t* len) {
+__global__ void __launch_bounds__(kThreads) block_len_kernel(const int32_t* ptr_all, const int32_t* idx, int nblk,
+                                                            int causal, int column_lists, int32_t* len_all) {
     const int i = blockIdx.x * kThreads + threadIdx.x;
     if (i >= nblk) return;
+    const int32_t* ptr = ptr_all + (long)blockIdx.y * (nblk + 1);  // mask blockIdx.y
+    int32_t* len = len_all + (long)blockIdx.y * nblk;
     const int first = ptr[i];
     int count = ptr[i + 1] - first;
     if (causal) {
@@ -60,9 +62,11 @@ __global__ void __launch_bounds__(kThreads) block_len_kernel(const int32_t* ptr,
     }
     len[i] = count;
 }
-__global__ void __launch_bounds__(kThreads) block_order_kernel(const int32_t* len, int nblk, int32_t* order) {
+__global__ void __launch_bounds__(kThreads) block_order_kernel(const int32_t* len_all, int nblk, int32_t* order_all) {
     const int i = blockIdx.x * kThreads + threadIdx.x;
     if (i >= nblk) return;
+    const int32_t* len = len_all + (long)blockIdx.y * nblk;
+    int32_t* order = order_all + (long)blockIdx.y * nblk;
     const int mine = len[i];
     int rank = 0;
     for (int k = 0; k < nblk; ++k) {
@@ -105,7 +109,7 @@ __global__ void __launch_bounds__(kThreads, D <= 128 ? 2 : 1) bwd_dkdv_kernel(Fu
     int bh, j;
     decode_block(blockIdx.x, key_blocks, p.batch * p.heads, bh, j);
     if (p.order) {
-        j = 2 * p.order[j >> 1] + (j & 1);
+        j = 2 * p.order[(long)bh * p.order_stride + (j >> 1)] + (j & 1);
         if (j * BC >= p.n) return;
     }
     const long base = (long)(bh / p.heads) * p.stride_b + (long)(bh % p.heads) * p.stride_h;
@@ -116,8 +120,9 @@ __global__ void __launch_bounds__(kThreads, D <= 128 ? 2 : 1) bwd_dkdv_kernel(Fu
 
     int n_it, t0 = 0, lp0 = 0;
     if (p.list_ptr) {
-        lp0 = p.list_ptr[j0 / 128];
-        int entries = p.list_ptr[j0 / 128 + 1] - lp0;
+        const int32_t* lptr = p.list_ptr + (long)bh * p.list_stride;  // this (batch, head)'s mask
+        lp0 = lptr[j0 / 128];
+        int entries = lptr[j0 / 128 + 1] - lp0;
         if (p.causal) {
             const int skip = causal_col_skip(p.list_idx, lp0, entries, j0 / 128);
             lp0 += skip;
@@ -389,7 +394,7 @@ __global__ void __launch_bounds__(kThreads, D == 64 ? 4 : (QT == 1 && D <= 128 ?
     int bh, blk;
     decode_block(blockIdx.x, q_blocks, p.batch * p.heads, bh, blk);
     // longest rows first: under the causal rule the last blocks, under a block mask by the order list
-    const int ib = p.order ? p.order[blk] : (p.causal ? q_blocks - 1 - blk : blk);
+    const int ib = p.order ? p.order[(long)bh * p.order_stride + blk] : (p.causal ? q_blocks - 1 - blk : blk);
     const long base = (long)(bh / p.heads) * p.stride_b + (long)(bh % p.heads) * p.stride_h;
     const long ld = p.stride_n;
     const int i0 = ib * BR;
@@ -397,8 +402,9 @@ __global__ void __launch_bounds__(kThreads, D == 64 ? 4 : (QT == 1 && D <= 128 ?
 
     int n_it, lp0 = 0;
     if (p.list_ptr) {  // block lists are per 128 queries: only with QT == 1
-        lp0 = p.list_ptr[ib];
-        int entries = p.list_ptr[ib + 1] - lp0;
+        const int32_t* lptr = p.list_ptr + (long)bh * p.list_stride;  // this (batch, head)'s mask
+        lp0 = lptr[ib];
+        int entries = lptr[ib + 1] - lp0;
         if (p.causal) entries = causal_row_entries(p.list_idx, lp0, entries, ib);
         n_it = entries * (128 / BC);
     } else {
@@ -623,11 +629,12 @@ static hipError_t launch_bwd(const FusedParams& p, const int32_t* csr_ptr, const
     const int blocks128 = (p.n + 127) / 128;
     int32_t* order_q = nullptr;
     int32_t* order_k = nullptr;
-    if (order_scratch && csr_ptr && csc_ptr) {
+    const int masks = p.list_stride ? bh : 1;  // one mask per (batch, head), or one for all
+    if (order_scratch && csr_ptr && csc_ptr && masks <= 65535) {  // (grid.y limit; beyond it: ascending order)
         order_q = order_scratch;
-        order_k = order_scratch + blocks128;
-        int32_t* len = order_scratch + 2 * blocks128;
-        const dim3 og((unsigned)((blocks128 + kThreads - 1) / kThreads));
+        order_k = order_scratch + (long)masks * blocks128;
+        int32_t* len = order_scratch + 2L * masks * blocks128;
+        const dim3 og((unsigned)((blocks128 + kThreads - 1) / kThreads), (unsigned)masks);
         hipLaunchKernelGGL(block_len_kernel, og, dim3(kThreads), 0, stream, csr_ptr, csr_idx, blocks128, p.causal, 0, len);
         hipLaunchKernelGGL(block_order_kernel, og, dim3(kThreads), 0, stream, len, blocks128, order_q);
         if (!dq_only) {
@@ -639,6 +646,7 @@ static hipError_t launch_bwd(const FusedParams& p, const int32_t* csr_ptr, const
     pq.list_ptr = csr_ptr;
     pq.list_idx = csr_idx;
     pq.order = order_q;
+    pq.order_stride = p.list_stride ? blocks128 : 0;
     // One query tile per wave and two workgroups per CU.  (QT = 2, i.e. one wave per SIMD with every
     // LDS fragment feeding two MFMAs, halves the LDS traffic but measured 20 % slower at d = 128:
     // with a single wave per SIMD the softmax arithmetic no longer overlaps another wave's MFMAs.)
@@ -648,6 +656,7 @@ static hipError_t launch_bwd(const FusedParams& p, const int32_t* csr_ptr, const
     pk.list_ptr = csc_ptr;
     pk.list_idx = csc_idx;
     pk.order = order_k;
+    pk.order_stride = p.list_stride ? blocks128 : 0;
     const int key_blocks = order_k ? 2 * blocks128 : (p.n + 63) / 64;
     hipLaunchKernelGGL(bwd_dkdv_kernel<D>, dim3((unsigned)(key_blocks * bh)), dim3(kThreads), kv_lds, stream, pk);
     return hipGetLastError();

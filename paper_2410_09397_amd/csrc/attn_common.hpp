@@ -348,6 +348,8 @@ struct FusedParams {
     // under a block mask, optionally: the 128-row blocks of the resident operand in the order the
     // workgroups take them (longest list first), nullptr = ascending
     const int32_t* order;
+    // masks per (batch, head): entries between the list_ptr (order) arrays of consecutive pairs; 0 = one shared mask
+    int list_stride, order_stride;
 };
 
 }  // namespace attn

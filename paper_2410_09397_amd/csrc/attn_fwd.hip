@@ -36,8 +36,9 @@ __global__ void __launch_bounds__(kThreads, D == 64 ? 4 : (D <= 128 ? 2 : 1)) fw
 
     int n_it, lp0 = 0;
     if (p.list_ptr) {
-        lp0 = p.list_ptr[ib];
-        int entries = p.list_ptr[ib + 1] - lp0;
+        const int32_t* lptr = p.list_ptr + (long)bh * p.list_stride;  // this (batch, head)'s mask
+        lp0 = lptr[ib];
+        int entries = lptr[ib + 1] - lp0;
         if (p.causal) entries = causal_row_entries(p.list_idx, lp0, entries, ib);
         n_it = entries * (128 / BC);
     } else {

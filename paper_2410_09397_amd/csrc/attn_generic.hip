@@ -67,7 +67,7 @@ __global__ void __launch_bounds__(kThreads) generic_fwd_kernel(GenericParams p) 
     T* O = (T*)p.O + base;
     for (int k = lane; k < p.d; k += 64) qs[w][k] = ldf(Q + (long)i * p.stride_n + k);
     __syncthreads();
-    const Ranges rg{p.csr_ptr, p.csr_idx, p.block, p.n, p.causal};
+    const Ranges rg{p.csr_ptr ? p.csr_ptr + (long)bh * p.mask_stride : nullptr, p.csr_idx, p.block, p.n, p.causal};
     const int nr = rg.count(i);
     float m = -__builtin_inff();
     for (int a = 0; a < nr; ++a) {
@@ -144,7 +144,7 @@ __global__ void __launch_bounds__(kThreads) generic_dq_kernel(GenericParams p) {
     }
     __syncthreads();
     const float lse = p.LSE_in[r], v = p.delta[r];
-    const Ranges rg{p.csr_ptr, p.csr_idx, p.block, p.n, p.causal};
+    const Ranges rg{p.csr_ptr ? p.csr_ptr + (long)bh * p.mask_stride : nullptr, p.csr_idx, p.block, p.n, p.causal};
     const int nr = rg.count(i);
     float acc[kCols];
 #pragma unroll
@@ -198,7 +198,7 @@ __global__ void __launch_bounds__(kThreads) generic_dkdv_kernel(GenericParams p)
         vs[w][k] = ldf(V + (long)j * p.stride_n + k);
     }
     __syncthreads();
-    const Ranges rg{p.csc_ptr, p.csc_idx, p.block, p.n, p.causal};
+    const Ranges rg{p.csc_ptr ? p.csc_ptr + (long)bh * p.mask_stride : nullptr, p.csc_idx, p.block, p.n, p.causal};
     const int nr = rg.count(j);
     float ak[kCols], av[kCols];
 #pragma unroll

@@ -10,7 +10,7 @@ namespace attn {
 hipError_t launch_fwd_fused(int d, const FusedParams& p, const int32_t* csr_ptr, const int32_t* csr_idx,
                             hipStream_t stream);
 // dq_only: run the query-owner kernel alone (dQ and delta), for callers that need neither dK nor dV.
-// order_scratch: under a block mask, 3 * ceil(n / 128) int32 of device scratch for the order in
+// order_scratch: under a block mask, 3 * ceil(n / 128) int32 per mask of device scratch for the order in
 // which the workgroups take the blocks (longest list first), or nullptr (ascending order).
 hipError_t launch_bwd_fused(int d, const FusedParams& p, const int32_t* csr_ptr, const int32_t* csr_idx,
                             const int32_t* csc_ptr, const int32_t* csc_idx, hipStream_t stream,
@@ -49,6 +49,7 @@ struct GenericParams {
     int causal;
     const int32_t *csr_ptr, *csr_idx, *csc_ptr, *csc_idx;  // nullptr = dense
     int block;
+    int mask_stride;  // entries between the pointer arrays of consecutive (batch, head) masks; 0 = one shared mask
 };
 hipError_t launch_generic(bool is_bf16, bool backward, const GenericParams& p, hipStream_t stream);
 

@@ -28,6 +28,7 @@ class Workload:
     block: int = 128
     extra_frac: float = 0.10
     dO_std: float = 1.0
+    per_head_masks: bool = False  # block-sparse: a different mask for every (batch, head) pair
 
     @property
     def scale(self):
@@ -116,10 +117,11 @@ def normal(shape, std, seed, workload_index, tensor, dtype):
     return round_to_bf16(x) if dtype == "bf16" else x
 
 
-def block_mask(nblk, extra, seed, workload_index):
+def block_mask(nblk, extra, seed, workload_index, pair=0):
     """[nblk, nblk] uint8: the diagonal block plus `extra` distinct other key blocks per
-    query-block row, drawn without replacement, uniformly, from the seeded stream."""
-    rng = _rng(seed, workload_index, TENSOR_IDS["mask"])
+    query-block row, drawn without replacement, uniformly, from the seeded stream (one stream
+    per (batch, head) pair when every pair has its own mask)."""
+    rng = _rng(seed, workload_index, TENSOR_IDS["mask"] + 16 * int(pair))
     keep = np.zeros((nblk, nblk), dtype=np.uint8)
     for i in range(nblk):
         keep[i, i] = 1
@@ -135,7 +137,11 @@ def make_inputs(w, seed=BASE_SEED):
     shape = (w.batch, w.heads, w.n, w.d)
     out = {t: normal(shape, w.dO_std if t == "dO" else 1.0, seed, w.index, t, w.dtype)
            for t in ("Q", "K", "V", "dO")}
-    out["keep"] = block_mask(w.nblk, w.extra_blocks, seed, w.index) if w.sparse else None
+    if w.sparse and w.per_head_masks:
+        out["keep"] = np.stack([block_mask(w.nblk, w.extra_blocks, seed, w.index, pair=m)
+                                for m in range(w.batch * w.heads)])
+    else:
+        out["keep"] = block_mask(w.nblk, w.extra_blocks, seed, w.index) if w.sparse else None
     return out
 
 

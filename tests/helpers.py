@@ -41,7 +41,23 @@ def round_storage(x, dtype):
 def oracle_reference(w, inp):
     """Oracle forward, then oracle backward fed with the O / LSE the GPU backward will be given
     in the isolated test (rounded to the storage type / to fp32)."""
-    m = dict(causal=w.causal, keep=inp["keep"], block=w.block)
+    keep = inp["keep"]
+    if keep is not None and np.asarray(keep).ndim == 3:
+        # one mask per (batch, head) pair: the oracle takes one mask per call, so it is called pair by pair
+        parts = []
+        for m in range(w.batch * w.heads):
+            b, h = divmod(m, w.heads)
+            one = {t: inp[t][b:b + 1, h:h + 1] for t in ("Q", "K", "V", "dO")}
+            one["keep"] = keep[m]
+            parts.append(oracle_reference(w, one))
+        def join(key, i=None):
+            xs = [p[key] if i is None else p[key][i] for p in parts]
+            return np.concatenate(xs, axis=1).reshape((w.batch, w.heads) + xs[0].shape[2:])
+        out = {k: join(k) for k in ("O", "LSE", "O_in", "LSE_in")}
+        out["iso"] = tuple(join("iso", i) for i in range(3))
+        out["exact"] = tuple(join("exact", i) for i in range(3))
+        return out
+    m = dict(causal=w.causal, keep=keep, block=w.block)
     O, LSE = orc.attn_fwd(inp["Q"], inp["K"], inp["V"], w.scale, **m)
     O_in = round_storage(O, w.dtype)
     LSE_in = LSE.astype(np.float32)

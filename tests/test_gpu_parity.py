@@ -38,6 +38,12 @@ CASES = [
     W("bf16_d128_sparse_ragged", 42, 1, 1, 1000, 128, "bf16", sparse=True, extra_frac=0.15),
     W("bf16_d64_sparse_causal", 43, 1, 2, 768, 64, "bf16", sparse=True, causal=True, extra_frac=0.5),
     W("bf16_d128_sparse_causal_ragged", 44, 1, 2, 1100, 128, "bf16", sparse=True, causal=True, extra_frac=0.4),
+    # one mask per (batch, head) pair: fused kernels and the generic ones
+    W("bf16_d128_masks_per_head", 45, 2, 3, 900, 128, "bf16", sparse=True, extra_frac=0.3, per_head_masks=True),
+    W("bf16_d64_masks_per_head_causal", 46, 1, 4, 640, 64, "bf16", sparse=True, causal=True, extra_frac=0.5,
+      per_head_masks=True),
+    W("f32_masks_per_head_blocks16", 47, 2, 2, 100, 32, "f32", sparse=True, block=16, extra_frac=0.3,
+      per_head_masks=True),
     # d = 256 (fused kernels, one wave per SIMD) and the large head dimensions (small-cache regime)
     W("bf16_d512", 51, 1, 2, 384, 512, "bf16"),
     W("bf16_d512_ragged_causal", 52, 1, 1, 200, 512, "bf16", causal=True),

@@ -142,6 +142,19 @@ def test_blockmask_validate_and_csr_csc():
     bad = rp.copy(); bad[3] = bad[2] - 1                          # non-monotone pointer
     assert v(128, 16, 2048, bad, ci, cp, ri) == attn.ATTN_ERR_INVALID_ARG
     assert v(0, 16, 2048, rp, ci, cp, ri) == attn.ATTN_ERR_INVALID_ARG
+    # a stack of masks, one per (batch, head) pair: pointer arrays continue from mask to mask
+    stack = np.stack([keep, np.roll(keep, 3, axis=1) | np.eye(16, dtype=keep.dtype), np.eye(16, dtype=keep.dtype)])
+    srp, sci, scp, sri = attn.csr_csc_from_dense(stack)
+    assert len(srp) == 3 * 17 and srp[17] == srp[16] and srp[-1] == len(sci) == len(sri)
+    assert v(128, 16, 2048, srp, sci, scp, sri, nmasks=3) == attn.ATTN_OK
+    bad = srp.copy(); bad[17:34] += 1                             # second mask does not continue the first
+    assert v(128, 16, 2048, bad, sci, scp, sri, nmasks=3) == attn.ATTN_ERR_INVALID_ARG
+    swapped = attn.csr_csc_from_dense(stack[[0, 2, 1]])           # orientations of masks 1 and 2 disagree
+    assert v(128, 16, 2048, srp, sci, swapped[2], swapped[3], nmasks=3) == attn.ATTN_ERR_INVALID_ARG
+    # the number of masks must be 1 or batch * heads
+    d = desc(n=2048, heads=2, stride_h=2048 * 64, stride_b=2 * 2048 * 64)
+    m = attn.attn_blockmask(128, 16, P, P, P, P, 3)
+    assert call_fwd(d, mask=ctypes.byref(m)) == attn.ATTN_ERR_INVALID_ARG
 
 
 def test_synthetic_inputs_are_reproducible_and_rounded():
