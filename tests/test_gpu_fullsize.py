@@ -26,9 +26,29 @@ def sample_rows(w, rng, count=40):
 
 @pytest.mark.parametrize("index", [1, 2, 3, 4, 5])
 def test_workload_at_full_size(index):
+    check_at_full_size(synth.workload(index), index)
+
+
+# Shapes beyond the five workloads, at sizes where every kernel runs many tiles per workgroup: the fused
+# kernels at d = 256 (one wave per SIMD), the four-phase path at d = 1024, block masks with the causal rule on
+# top, and one mask per (batch, head) pair.
+MORE = [
+    synth.Workload("full_d256_causal", 71, 1, 4, 4096, 256, "bf16", causal=True),
+    synth.Workload("full_d1024", 72, 1, 2, 2048, 1024, "bf16"),
+    synth.Workload("full_d128_sparse_causal", 73, 1, 4, 8192, 128, "bf16", sparse=True, causal=True, extra_frac=0.3),
+    synth.Workload("full_d128_masks_per_head", 74, 2, 2, 4096, 128, "bf16", sparse=True, extra_frac=0.25,
+                   per_head_masks=True),
+]
+
+
+@pytest.mark.parametrize("w", MORE, ids=lambda w: w.name)
+def test_more_shapes_at_scale(w):
+    check_at_full_size(w, w.index)
+
+
+def check_at_full_size(w, index):
     import torch
     from paper_2410_09397_amd import attn
-    w = synth.workload(index)
     print("workload", w, flush=True)
     inp = synth.make_inputs(w)
     Q, K, V, dO = (to_dev(inp[t], w.dtype) for t in ("Q", "K", "V", "dO"))
@@ -52,9 +72,10 @@ def test_workload_at_full_size(index):
     rng = np.random.default_rng(1000 + index)
     bh = w.batch * w.heads
     heads = sorted({0, bh - 1, int(rng.integers(0, bh))})
-    m = dict(causal=w.causal, keep=inp["keep"], block=w.block)
+    per_head = inp["keep"] is not None and np.asarray(inp["keep"]).ndim == 3
     for lin in heads:
         b, h = divmod(lin, w.heads)
+        m = dict(causal=w.causal, keep=inp["keep"][lin] if per_head else inp["keep"], block=w.block)
         q, k, v, g = (inp[t][b, h] for t in ("Q", "K", "V", "dO"))
         rO, rL = orc.attn_fwd(q[None, None], k[None, None], v[None, None], w.scale, **m)
         assert rel_err(to_np(O[b, h]), rO[0, 0]) <= tol, ("O", lin)
