@@ -53,19 +53,18 @@ def load_traffic(name):
         return json.load(fh).get(name)
 
 
-def mfma_ceiling(attn, torch, zero_operands, ms_target=60.0):
-    """Rate and clock of the library's register-only MFMA loop, run for about ms_target."""
+def mfma_ceiling(attn, torch, zero_operands, iters=150000):
+    """Rate and clock of the library's register-only MFMA loop: a short warm-up launch, then `iters`
+    iterations (about 40 ms at the clock random operands allow)."""
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    iters = 20000
-    for _ in range(2):  # the second run is sized from the first
-        e0.record()
-        clock, flops = attn.attn_mfma_ceiling(iters, zero_operands)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1)
-        last = {"tflops": flops / (ms * 1e-3) * 1e-12, "clock_ghz": float(clock.item()), "ms": ms, "iters": iters}
-        iters = max(1000, int(iters * ms_target / ms))
-    return last
+    attn.attn_mfma_ceiling(20000, zero_operands)
+    torch.cuda.synchronize()
+    e0.record()
+    clock, flops = attn.attn_mfma_ceiling(iters, zero_operands)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1)
+    return {"tflops": flops / (ms * 1e-3) * 1e-12, "clock_ghz": float(clock.item()), "ms": ms, "iters": iters}
 
 
 def main():
@@ -172,7 +171,7 @@ def main():
     if w.dtype == "bf16":
         # context for `frac`: what a register-only MFMA loop sustains on this GPU for random operands
         # (the clock under matrix load follows the power the data draws; `peak` assumes 2.4 GHz)
-        out["mfma_ceiling_random_operands"] = mfma_ceiling(attn, torch, False, ms_target=40.0)
+        out["mfma_ceiling_random_operands"] = mfma_ceiling(attn, torch, False)
     if args.wgrad and w.dtype == "bf16" and w.d in (64, 128, 256) and not w.sparse:
         del grads, O, ws
         wi = synth.make_wgrad_inputs(w)
