@@ -52,6 +52,11 @@ CASES = [
     W("bf16_d256_sparse_causal", 61, 1, 1, 512, 256, "bf16", sparse=True, causal=True, extra_frac=0.5),
     W("bf16_d512_causal_5blocks", 54, 1, 2, 640, 512, "bf16", causal=True, dO_std=0.1),
     W("bf16_d256_ragged_causal", 55, 2, 1, 333, 256, "bf16", causal=True),
+    # single rows and a few rows on every bf16 path
+    W("bf16_d128_one_row", 62, 1, 2, 1, 128, "bf16", causal=True),
+    W("bf16_d256_three_rows", 63, 2, 1, 3, 256, "bf16"),
+    W("bf16_d512_one_row", 64, 1, 1, 1, 512, "bf16"),
+    W("bf16_d1024_65_rows_causal", 65, 1, 1, 65, 1024, "bf16", causal=True),
     W("bf16_d1024", 58, 1, 1, 256, 1024, "bf16"),
     W("bf16_d1024_ragged_causal", 59, 1, 2, 150, 1024, "bf16", causal=True),
     # shapes only the generic fp32-FMA kernels take: bf16 with d outside {64,128,256,512},
