@@ -146,7 +146,7 @@ __global__ void __launch_bounds__(kThreads, D == 64 ? 4 : (D <= 128 ? 2 : 1)) fw
         // not equal to it: it moves (and O, l are rescaled) only when the maximum has grown by
         // more than kSlack, so p = exp2(s - m_run) stays below 2^kSlack and the final O / l and
         // m_run + log2(l) are unchanged.  After the first tiles of a row this almost never
-        // happens, which saves the 4 MT + 1 multiplications per lane and tile of the rescaling.
+        // happens, which saves the 16 MT + 1 multiplications per lane and tile of the rescaling.
         constexpr float kSlack = 8.f;
         const float cand = mx * cs;
         const bool grow = cand > m_run + kSlack;  // also the first finite maximum after -inf
