@@ -77,6 +77,9 @@ def main():
                                                   "the JSON line then names the derived workload")
     ap.add_argument("--extra-frac", type=float, default=None,
                     help="block-sparse workload only: share of non-diagonal key blocks kept per query-block row")
+    ap.add_argument("--tiling", type=int, default=0,
+                    help="attn_bwd_tiling of include/attn_mi355x.h (0 = the library's choice, 1 = two kernels, "
+                         "2 / 3 = one pass with 64 / 128 keys per workgroup)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--wgrad", action="store_true",
                     help="also time attn_bwd_wgrad (the paper's weight gradient) on the same shape and "
@@ -115,7 +118,7 @@ def main():
     O = torch.empty_like(Q)
     LSE = torch.empty(Q.shape[:3], dtype=torch.float32, device="cuda")
     grads = tuple(torch.empty_like(Q) for _ in range(3))
-    desc = attn._desc(Q, w.scale, w.causal)
+    desc = attn._desc(Q, w.scale, w.causal, args.tiling)
     ws = torch.empty(max(attn.attn_workspace_bytes(desc, mask), 256), dtype=torch.uint8, device="cuda")
 
     def step(ev=None):
@@ -123,9 +126,10 @@ def main():
         if ev:
             ev[0].record()
         if mask is not None:
-            attn.attn_bwd_blocksparse(Q, K, V, O, dO, LSE, w.scale, mask, causal=w.causal, out=grads, workspace=ws)
+            attn.attn_bwd_blocksparse(Q, K, V, O, dO, LSE, w.scale, mask, causal=w.causal, out=grads, workspace=ws,
+                                      tiling=args.tiling)
         else:
-            attn.attn_bwd(Q, K, V, O, dO, LSE, w.scale, causal=w.causal, out=grads, workspace=ws)
+            attn.attn_bwd(Q, K, V, O, dO, LSE, w.scale, causal=w.causal, out=grads, workspace=ws, tiling=args.tiling)
         if ev:
             ev[1].record()
 
@@ -159,7 +163,8 @@ def main():
         "vs_baseline": None, "dtype": w.dtype,
         "data": "all-zero operands (diagnostic, not a benchmark result)" if args.zero_operands else "synthetic",
         "config": {"workload": w.name, "batch": w.batch, "heads": w.heads, "n": w.n, "d": w.d,
-                   "causal": w.causal, "block_sparse": w.sparse, "step": "attn_fwd + attn_bwd"},
+                   "causal": w.causal, "block_sparse": w.sparse, "step": "attn_fwd + attn_bwd",
+                   "bwd_tiling": args.tiling},
         "bwd_ms": bwd_ms, "fwd_ms": fwd_ms, "fwd_tflops": w.fwd_flops() / (fwd_ms * 1e-3) * 1e-12,
         "step_tflops": (w.fwd_flops() + w.bwd_flops()) / (ms_per_step * 1e-3) * 1e-12,
         "roofline": {"bound": "mfma" if w.dtype == "bf16" else "alu", "kernel": "attn_bwd (all kernels of one call)",

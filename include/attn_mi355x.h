@@ -52,11 +52,34 @@ typedef enum {
 
 typedef enum { ATTN_F32 = 0, ATTN_BF16 = 1 } attn_dtype;
 
+/*
+ * Tilings of the fused bf16 backward (d in {64, 128, 256}).  All compute the same gradients; they
+ * differ in which block stays on chip, i.e. in the cache size M they need and in the traffic they
+ * cause (the trade-off of Thm 1.1 / Sec. 4), and exist side by side so that it can be measured.
+ *   ATTN_BWD_AUTO          the library's choice (the fastest measured for the shape)
+ *   ATTN_BWD_TWO_KERNEL    a query-block owner forms dQ and a key-block owner forms dK, dV; both
+ *                          recompute f and p (14 d multiply-adds per pair for 10 d counted); no
+ *                          atomics, every output bit-reproducible; d in {64, 128, 256}
+ *   ATTN_BWD_ONEPASS_K64   one key-block owner (64 keys) forms all five products once and adds its
+ *   ATTN_BWD_ONEPASS_K128  dQ tiles with fp32 atomic adds into a zeroed array in the workspace,
+ *                          which a last kernel scales and rounds to bf16 (K128: 128 keys per owner,
+ *                          half the atomic volume); dK, dV bit-reproducible, dQ up to the order of
+ *                          the additions; d in {64, 128}
+ * A tiling that does not exist for the shape gives ATTN_ERR_UNSUPPORTED; other paths ignore it.
+ */
+typedef enum {
+    ATTN_BWD_AUTO = 0,
+    ATTN_BWD_TWO_KERNEL = 1,
+    ATTN_BWD_ONEPASS_K64 = 2,
+    ATTN_BWD_ONEPASS_K128 = 3
+} attn_bwd_tiling;
+
 typedef struct {
     int32_t batch, heads, n, d;
-    float scale;    /* multiplies Q K^T; callers usually pass 1/sqrt(d) */
-    int32_t causal; /* 0 or 1: key j visible to query i iff j <= i */
-    int32_t dtype;  /* attn_dtype of Q, K, V, O, dO, dQ, dK, dV */
+    float scale;        /* multiplies Q K^T; callers usually pass 1/sqrt(d) */
+    int32_t causal;     /* 0 or 1: key j visible to query i iff j <= i */
+    int32_t dtype;      /* attn_dtype of Q, K, V, O, dO, dQ, dK, dV */
+    int32_t bwd_tiling; /* attn_bwd_tiling; 0 unless a particular tiling is to be measured */
     int64_t stride_b, stride_h, stride_n; /* in elements; the d axis has stride 1; stride_n < 2^22 */
 } attn_desc;
 
@@ -82,9 +105,10 @@ typedef struct {
 
 /* Bytes of device scratch that attn_fwd, attn_bwd and attn_bwd_blocksparse need for `desc`
  * (one figure that covers all three; 0 if desc or mask is invalid).  For d <= 256 it holds the
- * [batch, heads, n] row sums v (and, under a block mask, two lists of ceil(n / 128) block indices:
- * the order in which the workgroups take the blocks); for d > 256 (App. C path) also the n x n matrices f and p of
- * every (batch, head) in bf16, with n rounded up to 256. */
+ * [batch, heads, n] row sums v (under a block mask also two lists of ceil(n / 128) block indices:
+ * the order in which the workgroups take the blocks) and, for the one-pass tilings, the fp32
+ * [batch, heads, n, d] array in which dQ is summed; for d > 256 (App. C path) the row sums and
+ * the n x n matrices f and p of every (batch, head) in bf16, with n rounded up to 256. */
 size_t attn_workspace_bytes(const attn_desc *desc, const attn_blockmask *mask /* nullable */);
 
 /* Forward: writes O [batch, heads, n, d] and LSE [batch, heads, n].  `mask` may be NULL.

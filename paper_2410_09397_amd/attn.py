@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libattn_mi355x.so")
 
 ATTN_OK, ATTN_ERR_INVALID_ARG, ATTN_ERR_UNSUPPORTED, ATTN_ERR_WORKSPACE, ATTN_ERR_DEVICE = range(5)
 ATTN_F32, ATTN_BF16 = 0, 1
+ATTN_BWD_AUTO, ATTN_BWD_TWO_KERNEL, ATTN_BWD_ONEPASS_K64, ATTN_BWD_ONEPASS_K128 = range(4)
 
 EXPORTS = ("attn_workspace_bytes", "attn_fwd", "attn_bwd", "attn_bwd_blocksparse",
            "attn_wgrad_workspace_bytes", "attn_bwd_wgrad", "attn_blockmask_validate", "attn_mfma_ceiling",
@@ -24,8 +25,8 @@ EXPORTS = ("attn_workspace_bytes", "attn_fwd", "attn_bwd", "attn_bwd_blocksparse
 class attn_desc(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int32), ("heads", ctypes.c_int32), ("n", ctypes.c_int32),
                 ("d", ctypes.c_int32), ("scale", ctypes.c_float), ("causal", ctypes.c_int32),
-                ("dtype", ctypes.c_int32), ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64),
-                ("stride_n", ctypes.c_int64)]
+                ("dtype", ctypes.c_int32), ("bwd_tiling", ctypes.c_int32), ("stride_b", ctypes.c_int64),
+                ("stride_h", ctypes.c_int64), ("stride_n", ctypes.c_int64)]
 
 
 class attn_blockmask(ctypes.Structure):
@@ -128,13 +129,14 @@ class BlockMask:
         self.c = attn_blockmask(self.block, self.nblk, *[t.data_ptr() for t in self.dev], self.nmasks)
 
 
-def _desc(x, scale, causal):
+def _desc(x, scale, causal, tiling=ATTN_BWD_AUTO):
     import torch
     if x.dim() != 4 or x.stride(3) != 1:
         raise ValueError("expected a [batch, heads, n, d] tensor with unit stride along d")
     dt = {torch.float32: ATTN_F32, torch.bfloat16: ATTN_BF16}[x.dtype]
     b, h, n, d = x.shape
-    return attn_desc(b, h, n, d, float(scale), int(bool(causal)), dt, x.stride(0), x.stride(1), x.stride(2))
+    return attn_desc(b, h, n, d, float(scale), int(bool(causal)), dt, int(tiling), x.stride(0), x.stride(1),
+                     x.stride(2))
 
 
 def _same_layout(ref, *others):
@@ -176,10 +178,10 @@ def attn_fwd(Q, K, V, scale, causal=False, mask=None, stream=None, out=None, wor
     return O, LSE
 
 
-def _bwd(name, Q, K, V, O, dO, LSE, scale, causal, mask, stream, out, workspace):
+def _bwd(name, Q, K, V, O, dO, LSE, scale, causal, mask, stream, out, workspace, tiling):
     import torch
     _same_layout(Q, K, V, O, dO)
-    desc = _desc(Q, scale, causal)
+    desc = _desc(Q, scale, causal, tiling)
     dQ, dK, dV = out if out is not None else (torch.empty_like(Q), torch.empty_like(Q), torch.empty_like(Q))
     _same_layout(Q, dQ, dK, dV)
     if LSE.dtype != torch.float32 or not LSE.is_contiguous() or LSE.shape != Q.shape[:3]:
@@ -196,14 +198,16 @@ def _bwd(name, Q, K, V, O, dO, LSE, scale, causal, mask, stream, out, workspace)
     return dQ, dK, dV
 
 
-def attn_bwd(Q, K, V, O, dO, LSE, scale, causal=False, stream=None, out=None, workspace=None):
+def attn_bwd(Q, K, V, O, dO, LSE, scale, causal=False, stream=None, out=None, workspace=None,
+             tiling=ATTN_BWD_AUTO):
     """dQ, dK, dV from the forward's O and LSE (no block mask)."""
-    return _bwd("attn_bwd", Q, K, V, O, dO, LSE, scale, causal, None, stream, out, workspace)
+    return _bwd("attn_bwd", Q, K, V, O, dO, LSE, scale, causal, None, stream, out, workspace, tiling)
 
 
-def attn_bwd_blocksparse(Q, K, V, O, dO, LSE, scale, mask, causal=False, stream=None, out=None, workspace=None):
+def attn_bwd_blocksparse(Q, K, V, O, dO, LSE, scale, mask, causal=False, stream=None, out=None, workspace=None,
+                         tiling=ATTN_BWD_AUTO):
     """dQ, dK, dV under a BlockMask."""
-    return _bwd("attn_bwd_blocksparse", Q, K, V, O, dO, LSE, scale, causal, mask, stream, out, workspace)
+    return _bwd("attn_bwd_blocksparse", Q, K, V, O, dO, LSE, scale, causal, mask, stream, out, workspace, tiling)
 
 
 def attn_wgrad_workspace_bytes(desc):

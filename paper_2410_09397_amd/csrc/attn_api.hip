@@ -33,6 +33,7 @@ attn_status check_desc(const attn_desc* d) {
         return ATTN_ERR_INVALID_ARG;
     // the tile copies address a tile's rows with 32-bit byte offsets from its first row
     if (d->stride_n >= (int64_t)1 << 22) return ATTN_ERR_UNSUPPORTED;
+    if (d->bwd_tiling < ATTN_BWD_AUTO || d->bwd_tiling > ATTN_BWD_ONEPASS_K128) return ATTN_ERR_INVALID_ARG;
     return ATTN_OK;
 }
 
@@ -55,8 +56,21 @@ Path pick_path(const attn_desc* d, const attn_blockmask* m) {
     return Path::kGeneric;
 }
 
+// The tiling the fused backward runs with: the caller's choice where it exists for the shape (0 if it
+// does not), else the library's.
+int pick_tiling(const attn_desc* d) {
+    switch (d->bwd_tiling) {
+        case ATTN_BWD_TWO_KERNEL: return ATTN_BWD_TWO_KERNEL;
+        case ATTN_BWD_ONEPASS_K64: return (d->d == 64 || d->d == 128) ? ATTN_BWD_ONEPASS_K64 : 0;
+        case ATTN_BWD_ONEPASS_K128: return (d->d == 64 || d->d == 128) ? ATTN_BWD_ONEPASS_K128 : 0;
+        default: return ATTN_BWD_TWO_KERNEL;
+    }
+}
+bool is_onepass(int tiling) { return tiling == ATTN_BWD_ONEPASS_K64 || tiling == ATTN_BWD_ONEPASS_K128; }
+
 // d = 1024 exists on the large-d path only (the generic kernels stop at 512).
 attn_status check_path(const attn_desc* d, const attn_blockmask* m) {
+    if (pick_path(d, m) == Path::kFused && pick_tiling(d) == 0) return ATTN_ERR_UNSUPPORTED;
     return (d->d > 512 && pick_path(d, m) != Path::kLargeD) ? ATTN_ERR_UNSUPPORTED : ATTN_OK;
 }
 
@@ -65,6 +79,14 @@ size_t delta_bytes(const attn_desc* d) { return round_up((size_t)d->batch * d->h
 int mask_count(const attn_blockmask* m) { return m && m->nmasks > 1 ? m->nmasks : 1; }
 size_t order_bytes(const attn_desc* d, const attn_blockmask* m) {
     return round_up((size_t)mask_count(m) * 3 * (((size_t)d->n + 127) / 128) * sizeof(int32_t), 256);
+}
+// the fp32 [batch, heads, n, d] array in which the one-pass tilings sum dQ
+size_t dq_acc_bytes(const attn_desc* d) {
+    return round_up((size_t)d->batch * d->heads * d->n * d->d * sizeof(float), 256);
+}
+// Workspace layout of the fused backward: [delta][block order lists (masked only)][fp32 dQ (one-pass only)]
+size_t fused_bytes(const attn_desc* d, const attn_blockmask* m) {
+    return delta_bytes(d) + (m ? order_bytes(d, m) : 0) + (is_onepass(pick_tiling(d)) ? dq_acc_bytes(d) : 0);
 }
 
 // Workspace layout of the large-d path.  Backward: [delta][P][dS]; forward: [stat_m][stat_l][P].
@@ -160,10 +182,16 @@ attn_status bwd_impl(const attn_desc* desc, const attn_blockmask* mask, const vo
             p.LSE = LSE;
             p.delta = static_cast<float*>(workspace);
             p.list_stride = mask && mask->nmasks > 1 ? mask->nblk + 1 : 0;
+            char* ws = static_cast<char*>(workspace);
+            int32_t* order = mask ? reinterpret_cast<int32_t*>(ws + delta_bytes(desc)) : nullptr;
+            const int tiling = pick_tiling(desc);
+            float* dq_acc = is_onepass(tiling)
+                                ? reinterpret_cast<float*>(ws + delta_bytes(desc) + (mask ? order_bytes(desc, mask) : 0))
+                                : nullptr;
             e = attn::launch_bwd_fused(desc->d, p, mask ? mask->row_ptr : nullptr, mask ? mask->col_idx : nullptr,
-                                       mask ? mask->col_ptr : nullptr, mask ? mask->row_idx : nullptr, s, false,
-                                       mask ? reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + delta_bytes(desc))
-                                            : nullptr);
+                                       mask ? mask->col_ptr : nullptr, mask ? mask->row_idx : nullptr, s, false, order,
+                                       tiling == ATTN_BWD_ONEPASS_K64 ? 64 : tiling == ATTN_BWD_ONEPASS_K128 ? 128 : 0,
+                                       dq_acc);
             break;
         }
         case Path::kLargeD: {
@@ -250,7 +278,8 @@ size_t attn_workspace_bytes(const attn_desc* desc, const attn_blockmask* mask) {
         const size_t fwd = 2 * stat_bytes(desc) + nn_bytes(desc);
         return bwd > fwd ? bwd : fwd;
     }
-    return delta_bytes(desc) + (mask && pick_path(desc, mask) == Path::kFused ? order_bytes(desc, mask) : 0);
+    if (pick_path(desc, mask) == Path::kFused) return fused_bytes(desc, mask);
+    return delta_bytes(desc);
 }
 
 attn_status attn_fwd(const attn_desc* desc, const attn_blockmask* mask, const void* Q, const void* K,

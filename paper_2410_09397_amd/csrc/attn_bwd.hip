@@ -611,20 +611,20 @@ void launch_delta(const FusedParams& p, int d, hipStream_t stream) {
 template <int D>
 static hipError_t launch_bwd(const FusedParams& p, const int32_t* csr_ptr, const int32_t* csr_idx,
                              const int32_t* csc_ptr, const int32_t* csc_idx, hipStream_t stream, bool dq_only,
-                             int32_t* order_scratch) {
+                             int32_t* order_scratch, int onepass_keys, float* dq_acc) {
     const int bh = p.batch * p.heads;
+    const bool onepass = onepass_keys != 0 && !dq_only;
 
     constexpr int kv_lds = 2 * (2 * 64 * D * 2) + 2 * 64 * 64 * 2;  // two stages of Q, dO; P and dS
     constexpr int q_lds = 2 * (2 * 64 * D * 2);
     const void* kv_fn = reinterpret_cast<const void*>(bwd_dkdv_kernel<D>);
-    static bool configured = false;
-    if (!configured) {
+    // set on every call (the attribute belongs to the current device, and the call is cheap)
+    if (!onepass) {
         hipError_t e = hipFuncSetAttribute(kv_fn, hipFuncAttributeMaxDynamicSharedMemorySize, kv_lds);
         if (e != hipSuccess) return e;
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dq_kernel<D, 1>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, q_lds);
         if (e != hipSuccess) return e;
-        configured = true;
     }
     const int blocks128 = (p.n + 127) / 128;
     int32_t* order_q = nullptr;
@@ -635,12 +635,22 @@ static hipError_t launch_bwd(const FusedParams& p, const int32_t* csr_ptr, const
         order_k = order_scratch + (long)masks * blocks128;
         int32_t* len = order_scratch + 2L * masks * blocks128;
         const dim3 og((unsigned)((blocks128 + kThreads - 1) / kThreads), (unsigned)masks);
-        hipLaunchKernelGGL(block_len_kernel, og, dim3(kThreads), 0, stream, csr_ptr, csr_idx, blocks128, p.causal, 0, len);
-        hipLaunchKernelGGL(block_order_kernel, og, dim3(kThreads), 0, stream, len, blocks128, order_q);
+        if (!onepass) {
+            hipLaunchKernelGGL(block_len_kernel, og, dim3(kThreads), 0, stream, csr_ptr, csr_idx, blocks128, p.causal, 0, len);
+            hipLaunchKernelGGL(block_order_kernel, og, dim3(kThreads), 0, stream, len, blocks128, order_q);
+        }
         if (!dq_only) {
             hipLaunchKernelGGL(block_len_kernel, og, dim3(kThreads), 0, stream, csc_ptr, csc_idx, blocks128, p.causal, 1, len);
             hipLaunchKernelGGL(block_order_kernel, og, dim3(kThreads), 0, stream, len, blocks128, order_k);
         }
+    }
+    if (onepass) {
+        FusedParams pk = p;
+        pk.list_ptr = csc_ptr;
+        pk.list_idx = csc_idx;
+        pk.order = order_k;
+        pk.order_stride = p.list_stride ? blocks128 : 0;
+        return launch_bwd_onepass(D, onepass_keys, pk, dq_acc, stream);
     }
     FusedParams pq = p;
     pq.list_ptr = csr_ptr;
@@ -664,11 +674,11 @@ static hipError_t launch_bwd(const FusedParams& p, const int32_t* csr_ptr, const
 
 hipError_t launch_bwd_fused(int d, const FusedParams& p, const int32_t* csr_ptr, const int32_t* csr_idx,
                             const int32_t* csc_ptr, const int32_t* csc_idx, hipStream_t stream, bool dq_only,
-                            int32_t* order_scratch) {
+                            int32_t* order_scratch, int onepass_keys, float* dq_acc) {
     switch (d) {
-        case 64: return launch_bwd<64>(p, csr_ptr, csr_idx, csc_ptr, csc_idx, stream, dq_only, order_scratch);
-        case 128: return launch_bwd<128>(p, csr_ptr, csr_idx, csc_ptr, csc_idx, stream, dq_only, order_scratch);
-        case 256: return launch_bwd<256>(p, csr_ptr, csr_idx, csc_ptr, csc_idx, stream, dq_only, order_scratch);
+        case 64: return launch_bwd<64>(p, csr_ptr, csr_idx, csc_ptr, csc_idx, stream, dq_only, order_scratch, onepass_keys, dq_acc);
+        case 128: return launch_bwd<128>(p, csr_ptr, csr_idx, csc_ptr, csc_idx, stream, dq_only, order_scratch, onepass_keys, dq_acc);
+        case 256: return launch_bwd<256>(p, csr_ptr, csr_idx, csc_ptr, csc_idx, stream, dq_only, order_scratch, 0, nullptr);
         default: return hipErrorInvalidValue;
     }
 }

@@ -6,20 +6,26 @@
 
 namespace attn {
 
-// Fused bf16 paths, d in {64, 128}.  csr_* / csc_* are device pointers or nullptr (dense).
+// Fused bf16 paths, d in {64, 128, 256}.  csr_* / csc_* are device pointers or nullptr (dense).
 hipError_t launch_fwd_fused(int d, const FusedParams& p, const int32_t* csr_ptr, const int32_t* csr_idx,
                             hipStream_t stream);
 // dq_only: run the query-owner kernel alone (dQ and delta), for callers that need neither dK nor dV.
 // order_scratch: under a block mask, 3 * ceil(n / 128) int32 per mask of device scratch for the order in
 // which the workgroups take the blocks (longest list first), or nullptr (ascending order).
+// onepass_keys: 0 = the two-kernel tiling; 64 or 128 = the one-pass tiling with that many keys per
+// workgroup, which sums dQ in dq_acc, an fp32 [batch * heads, n, d] array of device scratch.
 hipError_t launch_bwd_fused(int d, const FusedParams& p, const int32_t* csr_ptr, const int32_t* csr_idx,
                             const int32_t* csc_ptr, const int32_t* csc_idx, hipStream_t stream,
-                            bool dq_only = false, int32_t* order_scratch = nullptr);
+                            bool dq_only = false, int32_t* order_scratch = nullptr, int onepass_keys = 0,
+                            float* dq_acc = nullptr);
+// The three launches of the one-pass tiling (d = 64: key_block 64; d = 128: 64 or 128); p.list_*, p.order
+// describe the key-block columns of a block mask (or are null).
+hipError_t launch_bwd_onepass(int d, int key_block, const FusedParams& p, float* dq_acc, hipStream_t stream);
 
 // delta[b, h, i] = sum_k dO_ik O_ik for bf16 tensors (p.O, p.dO, p.delta), any d % 8 == 0.
 void launch_delta(const FusedParams& p, int d, hipStream_t stream);
 
-// Arguments of the large-d path (bf16, d in {256, 512}, no block mask).  P and dS are n x n
+// Arguments of the large-d path (bf16, d in {512, 1024}, no block mask).  P and dS are n x n
 // matrices per (batch, head) with row pitch npad = n rounded up to 256, in the workspace.
 struct LargeDParams {
     const __bf16 *Q, *K, *V, *dO;
@@ -53,7 +59,7 @@ struct GenericParams {
 };
 hipError_t launch_generic(bool is_bf16, bool backward, const GenericParams& p, hipStream_t stream);
 
-// Weight gradient g = A_1^T dQ of the paper's loss (bf16, d in {64, 128}, contiguous tensors).
+// Weight gradient g = A_1^T dQ of the paper's loss (bf16, d in {64, 128, 256}, contiguous tensors).
 // Q, V, O, dQ are [b, h, n, d] bf16 scratch, LSE and delta [b, h, n] fp32, partial
 // [b * h, wgrad_chunks(n), d, d] fp32; X, Y are [b, h, d, d] bf16, g is [b, h, d, d] fp32.
 struct WgradParams {
