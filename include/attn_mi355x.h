@@ -122,6 +122,22 @@ attn_status attn_bwd(const attn_desc *desc, const void *Q, const void *K, const 
                      const void *O, const void *dO, const float *LSE, void *dQ, void *dK,
                      void *dV, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * attn_bwd for callers that cannot allocate or pass device scratch (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the same kernels and the same result as
+ * attn_bwd, with the scratch taken from a fixed array of ATTN_NOALLOC_SCRATCH_BYTES that the
+ * library holds on every GPU it runs on until the process ends.  It calls no hipMalloc, hipFree or
+ * other allocating routine.  A desc whose attn_workspace_bytes(desc, NULL) exceeds the array gives
+ * ATTN_ERR_WORKSPACE and launches nothing (d <= 256 needs 4 bytes per (batch, head, query) for the
+ * two-kernel tiling: 2 Mi rows fit).  Every call on one GPU uses that GPU's one array, which keeps
+ * the previous call's contents (nothing in it has to start at zero: every kernel writes what it
+ * later reads): calls that overlap in time on one GPU, on whatever streams, race.
+ */
+#define ATTN_NOALLOC_SCRATCH_BYTES (8u << 20)
+attn_status attn_bwd_noalloc(const attn_desc *desc, const void *Q, const void *K, const void *V,
+                             const void *O, const void *dO, const float *LSE, void *dQ, void *dK,
+                             void *dV, void *stream);
+
 /* Backward under a block mask (the sparse setting of Sec. 4.3; the paper gives bounds for it,
  * no algorithm).  `mask` must not be NULL.  Gradients of fully masked key rows are zero. */
 attn_status attn_bwd_blocksparse(const attn_desc *desc, const attn_blockmask *mask,

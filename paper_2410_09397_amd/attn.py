@@ -17,7 +17,7 @@ ATTN_OK, ATTN_ERR_INVALID_ARG, ATTN_ERR_UNSUPPORTED, ATTN_ERR_WORKSPACE, ATTN_ER
 ATTN_F32, ATTN_BF16 = 0, 1
 ATTN_BWD_AUTO, ATTN_BWD_TWO_KERNEL, ATTN_BWD_ONEPASS_K64, ATTN_BWD_ONEPASS_K128 = range(4)
 
-EXPORTS = ("attn_workspace_bytes", "attn_fwd", "attn_bwd", "attn_bwd_blocksparse",
+EXPORTS = ("attn_workspace_bytes", "attn_fwd", "attn_bwd", "attn_bwd_noalloc", "attn_bwd_blocksparse",
            "attn_wgrad_workspace_bytes", "attn_bwd_wgrad", "attn_blockmask_validate", "attn_mfma_ceiling",
            "attn_status_str")
 
@@ -59,6 +59,8 @@ def lib():
         L.attn_fwd.argtypes = [dp, mp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.attn_bwd.restype = ctypes.c_int
         L.attn_bwd.argtypes = [dp] + [vp] * 9 + [vp, ctypes.c_size_t, vp]
+        L.attn_bwd_noalloc.restype = ctypes.c_int
+        L.attn_bwd_noalloc.argtypes = [dp] + [vp] * 9 + [vp]
         L.attn_bwd_blocksparse.restype = ctypes.c_int
         L.attn_bwd_blocksparse.argtypes = [dp, mp] + [vp] * 9 + [vp, ctypes.c_size_t, vp]
         L.attn_wgrad_workspace_bytes.restype = ctypes.c_size_t
@@ -202,6 +204,22 @@ def attn_bwd(Q, K, V, O, dO, LSE, scale, causal=False, stream=None, out=None, wo
              tiling=ATTN_BWD_AUTO):
     """dQ, dK, dV from the forward's O and LSE (no block mask)."""
     return _bwd("attn_bwd", Q, K, V, O, dO, LSE, scale, causal, None, stream, out, workspace, tiling)
+
+
+def attn_bwd_noalloc(Q, K, V, O, dO, LSE, scale, out, causal=False, stream=None, tiling=ATTN_BWD_AUTO):
+    """attn_bwd with the library's fixed device scratch: the caller passes inputs and the outputs
+    out = (dQ, dK, dV); nothing is allocated here or in the library."""
+    import torch
+    _same_layout(Q, K, V, O, dO, *out)
+    desc = _desc(Q, scale, causal, tiling)
+    if LSE.dtype != torch.float32 or not LSE.is_contiguous() or LSE.shape != Q.shape[:3]:
+        raise ValueError("LSE must be a contiguous float32 [batch, heads, n] tensor")
+    st = lib().attn_bwd_noalloc(ctypes.byref(desc), Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
+                                dO.data_ptr(), LSE.data_ptr(), out[0].data_ptr(), out[1].data_ptr(),
+                                out[2].data_ptr(), _stream(stream))
+    if st != ATTN_OK:
+        raise AttnError(st, "attn_bwd_noalloc")
+    return out
 
 
 def attn_bwd_blocksparse(Q, K, V, O, dO, LSE, scale, mask, causal=False, stream=None, out=None, workspace=None,

@@ -3,10 +3,15 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "../../include/attn_mi355x.h"
 #include "attn_internal.hpp"
+
+// Device scratch of attn_bwd_noalloc: one copy per GPU the library runs on, held until the process
+// ends.  Host code never uses this name as an address; it asks the runtime for the device address.
+static __device__ __align__(256) unsigned char scratch[ATTN_NOALLOC_SCRATCH_BYTES];
 
 namespace {
 
@@ -265,6 +270,27 @@ WgradLayout wgrad_layout(const attn_desc* d) {
     return l;
 }
 
+// Device address of `scratch` on the current device, looked up once per device.
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void* scratch_ptr[kMaxDevices] = {};
+hipError_t scratch_address(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        scratch_ptr[dev] = ptr;
+    }
+    *out = scratch_ptr[dev];
+    return hipSuccess;
+}
+
 }  // namespace
 
 #pragma GCC visibility push(default)
@@ -344,6 +370,19 @@ attn_status attn_bwd(const attn_desc* desc, const void* Q, const void* K, const 
                      const void* dO, const float* LSE, void* dQ, void* dK, void* dV, void* workspace,
                      size_t workspace_bytes, void* stream) {
     return bwd_impl(desc, nullptr, Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, stream);
+}
+
+attn_status attn_bwd_noalloc(const attn_desc* desc, const void* Q, const void* K, const void* V, const void* O,
+                             const void* dO, const float* LSE, void* dQ, void* dK, void* dV, void* stream) {
+    attn_status st = check_desc(desc);
+    if (st != ATTN_OK) return st;
+    st = check_path(desc, nullptr);
+    if (st != ATTN_OK) return st;
+    if (is_empty(desc)) return ATTN_OK;
+    if (attn_workspace_bytes(desc, nullptr) > (size_t)ATTN_NOALLOC_SCRATCH_BYTES) return ATTN_ERR_WORKSPACE;
+    void* ptr = nullptr;
+    if (scratch_address(&ptr) != hipSuccess) return ATTN_ERR_DEVICE;
+    return bwd_impl(desc, nullptr, Q, K, V, O, dO, LSE, dQ, dK, dV, ptr, ATTN_NOALLOC_SCRATCH_BYTES, stream);
 }
 
 attn_status attn_bwd_blocksparse(const attn_desc* desc, const attn_blockmask* mask, const void* Q,
