@@ -44,13 +44,22 @@ def cpu_baseline(w, seconds_hint=20.0):
                                                 ", block-sparse" if ws.sparse else "", dt)}
 
 
-def load_traffic(name):
-    """HBM bytes per backward launch from the committed rocprofv3 --pmc summary, if there is one."""
+def load_traffic(name, tiling):
+    """HBM bytes of one backward call from the committed rocprofv3 --pmc summary, if there is one for this
+    workload and tiling, and whether the kernel sources have changed since it was measured.  The counters cannot be
+    read from inside this process: the figure is a recorded one (profiles/attn_kernels_<workload>.md gives the
+    commands that refresh it), and it is reported as stale when the hash stored with it no longer matches."""
+    from paper_2410_09397_amd import pmc_summary
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if not os.path.exists(path):
-        return None
+        return None, None
     with open(path) as fh:
-        return json.load(fh).get(name)
+        entry = json.load(fh).get(pmc_summary.traffic_key(name, tiling))
+    if entry is None:
+        return None, None
+    if not isinstance(entry, dict):  # a bare number: measured before hashes were stored
+        return float(entry), True
+    return float(entry["bytes"]), entry.get("source_hash") != pmc_summary.source_hash()
 
 
 def mfma_ceiling(attn, torch, zero_operands, iters=150000):
@@ -80,6 +89,8 @@ def main():
     ap.add_argument("--tiling", type=int, default=0,
                     help="attn_bwd_tiling of include/attn_mi355x.h (0 = the library's choice, 1 = two kernels, "
                          "2 / 3 = one pass with 64 / 128 keys per workgroup)")
+    ap.add_argument("--sustain", type=float, default=1.0,
+                    help="seconds of back-to-back steps after the timed ones for the `sustained` figure (0 = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--wgrad", action="store_true",
                     help="also time attn_bwd_wgrad (the paper's weight gradient) on the same shape and "
@@ -121,15 +132,18 @@ def main():
     desc = attn._desc(Q, w.scale, w.causal, args.tiling)
     ws = torch.empty(max(attn.attn_workspace_bytes(desc, mask), 256), dtype=torch.uint8, device="cuda")
 
+    def bwd(tiling):
+        if mask is not None:
+            attn.attn_bwd_blocksparse(Q, K, V, O, dO, LSE, w.scale, mask, causal=w.causal, out=grads, workspace=ws,
+                                      tiling=tiling)
+        else:
+            attn.attn_bwd(Q, K, V, O, dO, LSE, w.scale, causal=w.causal, out=grads, workspace=ws, tiling=tiling)
+
     def step(ev=None):
         attn.attn_fwd(Q, K, V, w.scale, causal=w.causal, mask=mask, out=(O, LSE), workspace=ws)
         if ev:
             ev[0].record()
-        if mask is not None:
-            attn.attn_bwd_blocksparse(Q, K, V, O, dO, LSE, w.scale, mask, causal=w.causal, out=grads, workspace=ws,
-                                      tiling=args.tiling)
-        else:
-            attn.attn_bwd(Q, K, V, O, dO, LSE, w.scale, causal=w.causal, out=grads, workspace=ws, tiling=args.tiling)
+        bwd(args.tiling)
         if ev:
             ev[1].record()
 
@@ -143,6 +157,44 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
+    bwd_times = sorted(a.elapsed_time(b) for a, b in events)
+    bwd_ms_mean = sum(bwd_times) / args.steps
+    bwd_ms = bwd_times[args.steps // 2] if args.steps % 2 else 0.5 * (bwd_times[args.steps // 2 - 1] + bwd_times[args.steps // 2])
+
+    # the same step back to back for at least a second after the timed steps: the clock of the part follows its
+    # power draw, and a window of a few milliseconds still sees the clock the idle part started from
+    sustained = None
+    if args.sustain > 0:
+        sev, t1 = [], time.perf_counter()
+        while time.perf_counter() - t1 < args.sustain and len(sev) < 20000:
+            batch = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
+            for ev in batch:
+                step(ev)
+            torch.cuda.synchronize()
+            sev += batch
+        st = sorted(a.elapsed_time(b) for a, b in sev)
+        sustained = {"seconds": time.perf_counter() - t1, "steps": len(sev), "bwd_ms_median": st[len(st) // 2],
+                     "bwd_ms_mean": sum(st) / len(st),
+                     "bwd_tflops": w.bwd_flops() / (st[len(st) // 2] * 1e-3) * 1e-12}
+
+    # the two kernels of the two-kernel tiling one at a time (the library runs one of them alone on request)
+    kernels = None
+    if w.dtype == "bf16" and w.d in (64, 128, 256) and args.tiling in (0, 1) and (not w.sparse or w.block == 128):
+        kernels = []
+        pairs = w.batch * w.heads * float(w.n) * w.n * w.kept_fraction()  # visible (query, key) pairs
+        for name, part, mults in (("bwd_dq_kernel (+ delta)", attn.ATTN_BWD_PART_DQ, 6), ("bwd_dkdv_kernel", attn.ATTN_BWD_PART_DKDV, 8)):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            bwd(part)
+            e0.record()
+            for _ in range(args.steps):
+                bwd(part)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / args.steps
+            ex = mults * w.d * pairs / (ms * 1e-3) * 1e-12
+            kernels.append({"kernel": name, "ms": ms, "flops_per_pair_executed": "%dd" % mults,
+                            "executed_tflops": ex, "frac_executed": ex / PEAK_TFLOPS["bf16"]})
+        bwd(args.tiling)  # leave the outputs of a whole call behind
     if args.calibrate_copy:
         src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")  # 1 GiB read + 1 GiB written
         dst = torch.empty_like(src)
@@ -150,12 +202,11 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    bwd_ms = sum(a.elapsed_time(b) for a, b in events) / args.steps
-    fwd_ms = ms_per_step - bwd_ms
+    fwd_ms = ms_per_step - bwd_ms_mean
     bwd_tflops = w.bwd_flops() / (bwd_ms * 1e-3) * 1e-12
 
     peak = PEAK_TFLOPS[w.dtype]
-    traffic = load_traffic(w.name)
+    traffic, traffic_stale = load_traffic(w.name, args.tiling)
     bound = io_bound.report(w)
     out = {
         "metric": METRIC, "value": bwd_tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -165,11 +216,16 @@ def main():
         "config": {"workload": w.name, "batch": w.batch, "heads": w.heads, "n": w.n, "d": w.d,
                    "causal": w.causal, "block_sparse": w.sparse, "step": "attn_fwd + attn_bwd",
                    "bwd_tiling": args.tiling},
-        "bwd_ms": bwd_ms, "fwd_ms": fwd_ms, "fwd_tflops": w.fwd_flops() / (fwd_ms * 1e-3) * 1e-12,
+        "value_is": "median over the timed steps of (algorithmic backward FLOPs / time between the HIP events around attn_bwd)",
+        "value_mean": w.bwd_flops() / (bwd_ms_mean * 1e-3) * 1e-12,
+        "bwd_ms": bwd_ms, "bwd_ms_mean": bwd_ms_mean, "bwd_ms_min": bwd_times[0], "bwd_ms_max": bwd_times[-1],
+        "sustained": sustained,
+        "fwd_ms": fwd_ms, "fwd_tflops": w.fwd_flops() / (fwd_ms * 1e-3) * 1e-12,
         "step_tflops": (w.fwd_flops() + w.bwd_flops()) / (ms_per_step * 1e-3) * 1e-12,
         "roofline": {"bound": "mfma" if w.dtype == "bf16" else "alu", "kernel": "attn_bwd (all kernels of one call)",
                      "achieved": bwd_tflops, "peak": peak, "unit": "TFLOP/s", "frac": bwd_tflops / peak,
-                     "traffic": traffic},
+                     "traffic": traffic, "traffic_source": "profiles/hbm_traffic.json (rocprofv3 --pmc, recorded)",
+                     "traffic_stale": traffic_stale, "kernels": kernels},
         "io_bound": bound,
         "traffic_over_yardstick": (traffic / bound["yardstick_bytes"]) if traffic else None,
     }

@@ -22,7 +22,9 @@
  *     all of them; LSE is contiguous [batch, heads, n] float.  Outputs are overwritten.
  *   - All work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream);
  *     calls return without synchronising.  The library allocates no device memory and keeps no
- *     state between calls; scratch comes from the caller's workspace (attn_workspace_bytes).
+ *     state between calls (attn_bwd_noalloc alone keeps the device address of its scratch array,
+ *     per GPU, behind a mutex); scratch comes from the caller's workspace (attn_workspace_bytes).
+ *     Entry points may be called from several host threads at once.
  *   - Arguments are validated on the host before anything is launched; a failed call launches
  *     nothing and leaves outputs untouched.  batch * heads * n == 0 is a valid empty call.
  *   - Supported: d a multiple of 8 for ATTN_BF16 (pointers and strides 16-byte aligned), any d
@@ -65,13 +67,20 @@ typedef enum { ATTN_F32 = 0, ATTN_BF16 = 1 } attn_dtype;
  *                          which a last kernel scales and rounds to bf16 (K128: 128 keys per owner,
  *                          half the atomic volume); dK, dV bit-reproducible, dQ up to the order of
  *                          the additions; d in {64, 128}
+ *   ATTN_BWD_PART_DQ       measurement aids: one kernel of ATTN_BWD_TWO_KERNEL alone, so that a caller
+ *   ATTN_BWD_PART_DKDV     can time it with events of its own.  PART_DQ writes dQ (and v into the
+ *                          workspace) and leaves dK, dV untouched; PART_DKDV writes dK, dV, leaves dQ
+ *                          untouched and reads the v (and, under a block mask, nothing else) that an
+ *                          earlier TWO_KERNEL or PART_DQ call left in the same workspace
  * A tiling that does not exist for the shape gives ATTN_ERR_UNSUPPORTED; other paths ignore it.
  */
 typedef enum {
     ATTN_BWD_AUTO = 0,
     ATTN_BWD_TWO_KERNEL = 1,
     ATTN_BWD_ONEPASS_K64 = 2,
-    ATTN_BWD_ONEPASS_K128 = 3
+    ATTN_BWD_ONEPASS_K128 = 3,
+    ATTN_BWD_PART_DQ = 4,
+    ATTN_BWD_PART_DKDV = 5
 } attn_bwd_tiling;
 
 typedef struct {

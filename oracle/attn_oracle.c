@@ -22,7 +22,8 @@
  *   - dV is not derived in the paper (Y is held fixed there); it follows from O = f h.
  *
  * Parity pins (tests/test_oracle_*.py): central finite differences of the forward loss,
- * the paper's own gradient g = A_1^T p A_2 evaluated by oracle_alg1_wgrad below,
+ * the paper's own gradient g = A_1^T p A_2 evaluated by oracle_wgrad below (and the same by
+ * the four-phase small-cache scheme, oracle_small_cache_wgrad),
  * closed forms (n = 1, Q = 0, causal first row), the zero row-sum of p, key-shift and
  * key-permutation invariances, and an independent library evaluation (softmax +
  * autograd in float64).  No function here is "parity unpinned".
@@ -248,49 +249,180 @@ static void matmul(int m, int n, int k, const double *A, int ta, const double *B
 }
 
 /*
- * The paper's own target, in the order of its no-cache algorithm (App. C.1):
- *   A = exp(A_1 X A_2^T); l = A 1; f = diag(l)^{-1} A; h = A_3 Y; q = dO h^T;
- *   p = f o q - diag((f o q) 1) f;  g = A_1^T p A_2   (definition of the backward gradient).
- * No scale, no mask, no max-subtraction (inputs must keep exp in range).  g is d x d;
- * f_out, q_out, p_out are NULL or n x n.
+ * The paper's own target (Def. 3.2): g = dL/dX = A_1^T p A_2, a d x d matrix, with
+ * S = A_1 X, h = A_3 Y and, per query row i (App. B.4, definitions of A, l, f, q, p):
+ *   f_ij = exp(<S_i, A_2j>) / sum_j' exp(<S_i, A_2j'>),  q_ij = <dO_i, h_j>,
+ *   v_i = sum_j f_ij q_ij,  p_ij = f_ij (q_ij - v_i).
+ * Evaluated row by row as g = sum_i A_1i^T (sum_j p_ij A_2j).  No scale, no mask and no
+ * max-subtraction, as in the paper (inputs must keep exp in range).  f_out, q_out, p_out are
+ * NULL or n x n.
  */
-void oracle_alg1_wgrad(int n, int d, const double *A1, const double *A2, const double *A3,
-                       const double *dO, const double *X, const double *Y, double *g,
-                       double *f_out, double *q_out, double *p_out)
+void oracle_wgrad(int n, int d, const double *A1, const double *A2, const double *A3,
+                  const double *dO, const double *X, const double *Y, double *g,
+                  double *f_out, double *q_out, double *p_out)
+{
+    size_t nd = (size_t)n * d;
+    double *S = (double *)malloc(sizeof(double) * nd);
+    double *h = (double *)malloc(sizeof(double) * nd);
+    double *f = (double *)malloc(sizeof(double) * (size_t)n);
+    double *q = (double *)malloc(sizeof(double) * (size_t)n);
+    double *u = (double *)malloc(sizeof(double) * (size_t)d);
+    matmul(n, d, d, A1, 0, X, 0, S);
+    matmul(n, d, d, A3, 0, Y, 0, h);
+    for (int a = 0; a < d * d; ++a)
+        g[a] = 0.0;
+    for (int i = 0; i < n; ++i) {
+        double l = 0.0, v = 0.0;
+        for (int j = 0; j < n; ++j) {
+            f[j] = exp(dot(S + (size_t)i * d, A2 + (size_t)j * d, d));
+            l += f[j];
+        }
+        for (int j = 0; j < n; ++j) {
+            f[j] /= l;
+            q[j] = dot(dO + (size_t)i * d, h + (size_t)j * d, d);
+            v += f[j] * q[j];
+        }
+        for (int k = 0; k < d; ++k)
+            u[k] = 0.0;
+        for (int j = 0; j < n; ++j) {
+            double p = f[j] * (q[j] - v);
+            for (int k = 0; k < d; ++k)
+                u[k] += p * A2[(size_t)j * d + k];
+            if (f_out) f_out[(size_t)i * n + j] = f[j];
+            if (q_out) q_out[(size_t)i * n + j] = q[j];
+            if (p_out) p_out[(size_t)i * n + j] = p;
+        }
+        for (int a = 0; a < d; ++a)
+            for (int k = 0; k < d; ++k)
+                g[(size_t)a * d + k] += A1[(size_t)i * d + a] * u[k];
+    }
+    free(S); free(h); free(f); free(q); free(u);
+}
+
+/*
+ * The same g by the small-cache scheme of App. C: four phases over B x B blocks, every n x n
+ * intermediate (A, f, q, p) and the d x n matrix T passing through memory, so that no more than
+ * a few B x B blocks are ever needed at once (the paper takes B = floor(sqrt(M / 4))).  Written
+ * as blocked loops of our own; what is kept from the paper is the phase structure:
+ *   phase 1: S = A_1 X;  A = exp(S A_2^T) with the row sums l gathered on the way;  f = A / l
+ *   phase 2: h = A_3 Y;  q = dO h^T
+ *   phase 3: v = rowsum(f o q);  p = f o q - diag(v) f
+ *   phase 4: T = A_1^T p;  g = T A_2
+ * Every product is a block product with a k-loop whose accumulator block stays in cache.
+ * io[0] / io[1] receive the number of elements read from / written to memory (blocks at the
+ * ragged edge count with their real size; the row vectors l and v count once per row block
+ * and sweep).  Pinned by equality with oracle_wgrad for block edges that do and do not
+ * divide n and d, and by the closed-form count of its own schedule.
+ */
+typedef struct { long long rd, wr; } io_count;
+
+static int bmin(int a, int b) { return a < b ? a : b; }
+
+/* C[m x n] = A B (or with transposes) in B x B blocks with the k-loop innermost; counts the
+ * block transfers: per output block, 2 operand blocks per k-step in, one block out. */
+static void blocked_matmul(int m, int n, int k, int B, const double *A, int ta, const double *Bm,
+                           int tb, double *C, io_count *io)
+{
+    for (int i0 = 0; i0 < m; i0 += B)
+        for (int j0 = 0; j0 < n; j0 += B) {
+            int mi = bmin(B, m - i0), nj = bmin(B, n - j0);
+            for (int i = 0; i < mi; ++i)
+                for (int j = 0; j < nj; ++j)
+                    C[(size_t)(i0 + i) * n + j0 + j] = 0.0;
+            for (int k0 = 0; k0 < k; k0 += B) {
+                int kk = bmin(B, k - k0);
+                io->rd += (long long)mi * kk + (long long)kk * nj;
+                for (int i = 0; i < mi; ++i)
+                    for (int j = 0; j < nj; ++j) {
+                        double acc = 0.0;
+                        for (int t = 0; t < kk; ++t) {
+                            double a = ta ? A[(size_t)(k0 + t) * m + i0 + i] : A[(size_t)(i0 + i) * k + k0 + t];
+                            double b = tb ? Bm[(size_t)(j0 + j) * k + k0 + t] : Bm[(size_t)(k0 + t) * n + j0 + j];
+                            acc += a * b;
+                        }
+                        C[(size_t)(i0 + i) * n + j0 + j] += acc;
+                    }
+            }
+            io->wr += (long long)mi * nj;
+        }
+}
+
+void oracle_small_cache_wgrad(int n, int d, int B, const double *A1, const double *A2,
+                              const double *A3, const double *dO, const double *X, const double *Y,
+                              double *g, long long *io_out)
 {
     size_t nn = (size_t)n * n, nd = (size_t)n * d;
+    io_count io = {0, 0};
     double *S = (double *)malloc(sizeof(double) * nd);
-    double *A = (double *)malloc(sizeof(double) * nn);
-    double *l = (double *)malloc(sizeof(double) * (size_t)n);
     double *h = (double *)malloc(sizeof(double) * nd);
+    double *f = (double *)malloc(sizeof(double) * nn);
     double *q = (double *)malloc(sizeof(double) * nn);
     double *p = (double *)malloc(sizeof(double) * nn);
     double *T = (double *)malloc(sizeof(double) * nd);
-    matmul(n, d, d, A1, 0, X, 0, S);  /* S = A_1 X */
-    matmul(n, n, d, S, 0, A2, 1, A);  /* A = S A_2^T */
-    for (size_t t = 0; t < nn; ++t)
-        A[t] = exp(A[t]);
-    for (int i = 0; i < n; ++i) {
-        l[i] = 0.0;
-        for (int j = 0; j < n; ++j)
-            l[i] += A[(size_t)i * n + j];
+    double *l = (double *)malloc(sizeof(double) * (size_t)n);
+    double *v = (double *)malloc(sizeof(double) * (size_t)n);
+    /* phase 1 */
+    blocked_matmul(n, d, d, B, A1, 0, X, 0, S, &io);
+    blocked_matmul(n, n, d, B, S, 0, A2, 1, f, &io);     /* f holds S A_2^T, block by block */
+    for (int i0 = 0; i0 < n; i0 += B) {                  /* exp and row sums: one more pass over the blocks */
+        int mi = bmin(B, n - i0);
+        for (int i = 0; i < mi; ++i)
+            l[i0 + i] = 0.0;
+        for (int j0 = 0; j0 < n; j0 += B) {
+            int nj = bmin(B, n - j0);
+            io.rd += (long long)mi * nj;
+            for (int i = 0; i < mi; ++i)
+                for (int j = 0; j < nj; ++j) {
+                    double a = exp(f[(size_t)(i0 + i) * n + j0 + j]);
+                    f[(size_t)(i0 + i) * n + j0 + j] = a;
+                    l[i0 + i] += a;
+                }
+            io.wr += (long long)mi * nj;
+        }
+        io.wr += mi;                                     /* l of this row block */
     }
-    for (int i = 0; i < n; ++i)
-        for (int j = 0; j < n; ++j)
-            A[(size_t)i * n + j] /= l[i]; /* A now holds f */
-    matmul(n, d, d, A3, 0, Y, 0, h);  /* h = A_3 Y */
-    matmul(n, n, d, dO, 0, h, 1, q);  /* q = dO h^T */
-    for (int i = 0; i < n; ++i) {
-        double v = 0.0;
-        for (int j = 0; j < n; ++j)
-            v += A[(size_t)i * n + j] * q[(size_t)i * n + j];
-        for (int j = 0; j < n; ++j)
-            p[(size_t)i * n + j] = A[(size_t)i * n + j] * q[(size_t)i * n + j] - v * A[(size_t)i * n + j];
+    for (int i0 = 0; i0 < n; i0 += B) {                  /* f = A / l */
+        int mi = bmin(B, n - i0);
+        io.rd += mi;
+        for (int j0 = 0; j0 < n; j0 += B) {
+            int nj = bmin(B, n - j0);
+            io.rd += (long long)mi * nj;
+            for (int i = 0; i < mi; ++i)
+                for (int j = 0; j < nj; ++j)
+                    f[(size_t)(i0 + i) * n + j0 + j] /= l[i0 + i];
+            io.wr += (long long)mi * nj;
+        }
     }
-    matmul(d, n, n, A1, 1, p, 0, T);  /* T = A_1^T p  (d x n) */
-    matmul(d, d, n, T, 0, A2, 0, g);  /* g = T A_2 */
-    if (f_out) memcpy(f_out, A, sizeof(double) * nn);
-    if (q_out) memcpy(q_out, q, sizeof(double) * nn);
-    if (p_out) memcpy(p_out, p, sizeof(double) * nn);
-    free(S); free(A); free(l); free(h); free(q); free(p); free(T);
+    /* phase 2 */
+    blocked_matmul(n, d, d, B, A3, 0, Y, 0, h, &io);
+    blocked_matmul(n, n, d, B, dO, 0, h, 1, q, &io);
+    /* phase 3: two sweeps over each row block */
+    for (int i0 = 0; i0 < n; i0 += B) {
+        int mi = bmin(B, n - i0);
+        for (int i = 0; i < mi; ++i)
+            v[i0 + i] = 0.0;
+        for (int j0 = 0; j0 < n; j0 += B) {
+            int nj = bmin(B, n - j0);
+            io.rd += 2LL * mi * nj;
+            for (int i = 0; i < mi; ++i)
+                for (int j = 0; j < nj; ++j)
+                    v[i0 + i] += f[(size_t)(i0 + i) * n + j0 + j] * q[(size_t)(i0 + i) * n + j0 + j];
+        }
+        for (int j0 = 0; j0 < n; j0 += B) {
+            int nj = bmin(B, n - j0);
+            io.rd += 2LL * mi * nj;
+            for (int i = 0; i < mi; ++i)
+                for (int j = 0; j < nj; ++j) {
+                    size_t a = (size_t)(i0 + i) * n + j0 + j;
+                    p[a] = f[a] * q[a] - v[i0 + i] * f[a];
+                }
+            io.wr += (long long)mi * nj;
+        }
+    }
+    /* phase 4 */
+    blocked_matmul(d, n, n, B, A1, 1, p, 0, T, &io);
+    blocked_matmul(d, d, n, B, T, 0, A2, 0, g, &io);
+    io_out[0] = io.rd;
+    io_out[1] = io.wr;
+    free(S); free(h); free(f); free(q); free(p); free(T); free(l); free(v);
 }

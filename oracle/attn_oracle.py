@@ -38,7 +38,7 @@ def _load():
     if _lib is None:
         _lib = ctypes.CDLL(build())
         for name in ("oracle_attn_fwd", "oracle_attn_bwd", "oracle_attn_bwd_head",
-                     "oracle_attn_bwd_sampled", "oracle_alg1_wgrad"):
+                     "oracle_attn_bwd_sampled", "oracle_wgrad", "oracle_small_cache_wgrad"):
             getattr(_lib, name).restype = None
     return _lib
 
@@ -114,12 +114,24 @@ def attn_bwd_sampled(Q, K, V, O, dO, LSE, scale, q_rows, k_rows, causal=False, k
     return dQ, dK, dV
 
 
-def alg1_wgrad(A1, A2, A3, dO, X, Y):
+def wgrad(A1, A2, A3, dO, X, Y):
     """The paper's weight gradient g = A_1^T p A_2 (d x d) and its f, q, p (n x n)."""
     A1, A2, A3, dO, X, Y = map(_f64, (A1, A2, A3, dO, X, Y))
     n, d = A1.shape
     g = np.empty((d, d))
     f, q, p = (np.empty((n, n)) for _ in range(3))
-    _load().oracle_alg1_wgrad(n, d, _d(A1), _d(A2), _d(A3), _d(dO), _d(X), _d(Y), _d(g),
-                              _d(f), _d(q), _d(p))
+    _load().oracle_wgrad(n, d, _d(A1), _d(A2), _d(A3), _d(dO), _d(X), _d(Y), _d(g),
+                         _d(f), _d(q), _d(p))
     return g, f, q, p
+
+
+def small_cache_wgrad(A1, A2, A3, dO, X, Y, B):
+    """The same g by the four-phase small-cache scheme over B x B blocks, and the number of
+    elements it reads from / writes to memory: (g, reads, writes)."""
+    A1, A2, A3, dO, X, Y = map(_f64, (A1, A2, A3, dO, X, Y))
+    n, d = A1.shape
+    g = np.empty((d, d))
+    io = (ctypes.c_longlong * 2)(0, 0)
+    _load().oracle_small_cache_wgrad(n, d, int(B), _d(A1), _d(A2), _d(A3), _d(dO), _d(X), _d(Y),
+                                     _d(g), io)
+    return g, int(io[0]), int(io[1])

@@ -15,7 +15,8 @@ LIB_PATH = os.path.join(_HERE, "libattn_mi355x.so")
 
 ATTN_OK, ATTN_ERR_INVALID_ARG, ATTN_ERR_UNSUPPORTED, ATTN_ERR_WORKSPACE, ATTN_ERR_DEVICE = range(5)
 ATTN_F32, ATTN_BF16 = 0, 1
-ATTN_BWD_AUTO, ATTN_BWD_TWO_KERNEL, ATTN_BWD_ONEPASS_K64, ATTN_BWD_ONEPASS_K128 = range(4)
+(ATTN_BWD_AUTO, ATTN_BWD_TWO_KERNEL, ATTN_BWD_ONEPASS_K64, ATTN_BWD_ONEPASS_K128, ATTN_BWD_PART_DQ,
+ ATTN_BWD_PART_DKDV) = range(6)
 
 EXPORTS = ("attn_workspace_bytes", "attn_fwd", "attn_bwd", "attn_bwd_noalloc", "attn_bwd_blocksparse",
            "attn_wgrad_workspace_bytes", "attn_bwd_wgrad", "attn_blockmask_validate", "attn_mfma_ceiling",
@@ -156,10 +157,18 @@ def attn_workspace_bytes(desc, mask=None):
     return lib().attn_workspace_bytes(ctypes.byref(desc), ctypes.byref(mask.c) if mask is not None else None)
 
 
-def _workspace(desc, mask, workspace, device):
+def _workspace(desc, mask, workspace, device, stream=None):
+    """The caller's workspace, or a fresh one.  A fresh one is allocated on the stream the kernels will
+    run on: torch's allocator may hand a freed block to later work of the allocating stream only, so the
+    block cannot be reused while these kernels still read it."""
     import torch
     if workspace is None:
-        workspace = torch.empty(max(attn_workspace_bytes(desc, mask), 256), dtype=torch.uint8, device=device)
+        nbytes = max(attn_workspace_bytes(desc, mask), 256)
+        if stream is not None:
+            with torch.cuda.stream(stream):
+                workspace = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        else:
+            workspace = torch.empty(nbytes, dtype=torch.uint8, device=device)
     return workspace
 
 
@@ -168,7 +177,7 @@ def attn_fwd(Q, K, V, scale, causal=False, mask=None, stream=None, out=None, wor
     import torch
     _same_layout(Q, K, V)
     desc = _desc(Q, scale, causal)
-    workspace = _workspace(desc, mask, workspace, Q.device)
+    workspace = _workspace(desc, mask, workspace, Q.device, stream)
     O = out[0] if out is not None else torch.empty_like(Q)
     LSE = out[1] if out is not None else torch.empty(Q.shape[:3], dtype=torch.float32, device=Q.device)
     _same_layout(Q, O)
@@ -188,7 +197,7 @@ def _bwd(name, Q, K, V, O, dO, LSE, scale, causal, mask, stream, out, workspace,
     _same_layout(Q, dQ, dK, dV)
     if LSE.dtype != torch.float32 or not LSE.is_contiguous() or LSE.shape != Q.shape[:3]:
         raise ValueError("LSE must be a contiguous float32 [batch, heads, n] tensor")
-    workspace = _workspace(desc, mask, workspace, Q.device)
+    workspace = _workspace(desc, mask, workspace, Q.device, stream)
     args = [Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), dO.data_ptr(), LSE.data_ptr(),
             dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream(stream)]
     if name == "attn_bwd":
@@ -243,7 +252,12 @@ def attn_bwd_wgrad(A1, A2, A3, X, Y, dO, scale=1.0, causal=False, stream=None, o
         raise ValueError("X and Y must be contiguous [batch, heads, d, d] tensors of the inputs' dtype")
     g = out if out is not None else torch.empty((b, h, d, d), dtype=torch.float32, device=A1.device)
     if workspace is None:
-        workspace = torch.empty(max(attn_wgrad_workspace_bytes(desc), 256), dtype=torch.uint8, device=A1.device)
+        nbytes = max(attn_wgrad_workspace_bytes(desc), 256)
+        if stream is not None:  # see _workspace
+            with torch.cuda.stream(stream):
+                workspace = torch.empty(nbytes, dtype=torch.uint8, device=A1.device)
+        else:
+            workspace = torch.empty(nbytes, dtype=torch.uint8, device=A1.device)
     st = lib().attn_bwd_wgrad(ctypes.byref(desc), A1.data_ptr(), A2.data_ptr(), A3.data_ptr(), X.data_ptr(),
                               Y.data_ptr(), dO.data_ptr(), g.data_ptr(), workspace.data_ptr(), workspace.numel(),
                               _stream(stream))

@@ -38,7 +38,7 @@ attn_status check_desc(const attn_desc* d) {
         return ATTN_ERR_INVALID_ARG;
     // the tile copies address a tile's rows with 32-bit byte offsets from its first row
     if (d->stride_n >= (int64_t)1 << 22) return ATTN_ERR_UNSUPPORTED;
-    if (d->bwd_tiling < ATTN_BWD_AUTO || d->bwd_tiling > ATTN_BWD_ONEPASS_K128) return ATTN_ERR_INVALID_ARG;
+    if (d->bwd_tiling < ATTN_BWD_AUTO || d->bwd_tiling > ATTN_BWD_PART_DKDV) return ATTN_ERR_INVALID_ARG;
     return ATTN_OK;
 }
 
@@ -65,7 +65,9 @@ Path pick_path(const attn_desc* d, const attn_blockmask* m) {
 // does not), else the library's.
 int pick_tiling(const attn_desc* d) {
     switch (d->bwd_tiling) {
-        case ATTN_BWD_TWO_KERNEL: return ATTN_BWD_TWO_KERNEL;
+        case ATTN_BWD_TWO_KERNEL:
+        case ATTN_BWD_PART_DQ:
+        case ATTN_BWD_PART_DKDV: return d->bwd_tiling;
         case ATTN_BWD_ONEPASS_K64: return (d->d == 64 || d->d == 128) ? ATTN_BWD_ONEPASS_K64 : 0;
         case ATTN_BWD_ONEPASS_K128: return (d->d == 64 || d->d == 128) ? ATTN_BWD_ONEPASS_K128 : 0;
         default: return ATTN_BWD_TWO_KERNEL;
@@ -194,12 +196,14 @@ attn_status bwd_impl(const attn_desc* desc, const attn_blockmask* mask, const vo
                                 ? reinterpret_cast<float*>(ws + delta_bytes(desc) + (mask ? order_bytes(desc, mask) : 0))
                                 : nullptr;
             e = attn::launch_bwd_fused(desc->d, p, mask ? mask->row_ptr : nullptr, mask ? mask->col_idx : nullptr,
-                                       mask ? mask->col_ptr : nullptr, mask ? mask->row_idx : nullptr, s, false, order,
+                                       mask ? mask->col_ptr : nullptr, mask ? mask->row_idx : nullptr, s,
+                                       tiling == ATTN_BWD_PART_DQ, order,
                                        tiling == ATTN_BWD_ONEPASS_K64 ? 64 : tiling == ATTN_BWD_ONEPASS_K128 ? 128 : 0,
-                                       dq_acc);
+                                       dq_acc, tiling == ATTN_BWD_PART_DKDV);
             break;
         }
         case Path::kLargeD: {
+            if (attn::configure_larged() != hipSuccess) return ATTN_ERR_DEVICE;  // before the first launch
             char* ws = static_cast<char*>(workspace);
             FusedParams fp = fused_params(desc);
             fp.O = static_cast<const __bf16*>(O);

@@ -611,7 +611,7 @@ void launch_delta(const FusedParams& p, int d, hipStream_t stream) {
 template <int D>
 static hipError_t launch_bwd(const FusedParams& p, const int32_t* csr_ptr, const int32_t* csr_idx,
                              const int32_t* csc_ptr, const int32_t* csc_idx, hipStream_t stream, bool dq_only,
-                             int32_t* order_scratch, int onepass_keys, float* dq_acc) {
+                             int32_t* order_scratch, int onepass_keys, float* dq_acc, bool dkdv_only) {
     const int bh = p.batch * p.heads;
     const bool onepass = onepass_keys != 0 && !dq_only;
 
@@ -635,7 +635,7 @@ static hipError_t launch_bwd(const FusedParams& p, const int32_t* csr_ptr, const
         order_k = order_scratch + (long)masks * blocks128;
         int32_t* len = order_scratch + 2L * masks * blocks128;
         const dim3 og((unsigned)((blocks128 + kThreads - 1) / kThreads), (unsigned)masks);
-        if (!onepass) {
+        if (!onepass && !dkdv_only) {
             hipLaunchKernelGGL(block_len_kernel, og, dim3(kThreads), 0, stream, csr_ptr, csr_idx, blocks128, p.causal, 0, len);
             hipLaunchKernelGGL(block_order_kernel, og, dim3(kThreads), 0, stream, len, blocks128, order_q);
         }
@@ -660,7 +660,8 @@ static hipError_t launch_bwd(const FusedParams& p, const int32_t* csr_ptr, const
     // One query tile per wave and two workgroups per CU.  (QT = 2, i.e. one wave per SIMD with every
     // LDS fragment feeding two MFMAs, halves the LDS traffic but measured 20 % slower at d = 128:
     // with a single wave per SIMD the softmax arithmetic no longer overlaps another wave's MFMAs.)
-    hipLaunchKernelGGL((bwd_dq_kernel<D, 1>), dim3((unsigned)(blocks128 * bh)), dim3(kThreads), q_lds, stream, pq);
+    if (!dkdv_only)
+        hipLaunchKernelGGL((bwd_dq_kernel<D, 1>), dim3((unsigned)(blocks128 * bh)), dim3(kThreads), q_lds, stream, pq);
     if (dq_only) return hipGetLastError();
     FusedParams pk = p;
     pk.list_ptr = csc_ptr;
@@ -674,11 +675,11 @@ static hipError_t launch_bwd(const FusedParams& p, const int32_t* csr_ptr, const
 
 hipError_t launch_bwd_fused(int d, const FusedParams& p, const int32_t* csr_ptr, const int32_t* csr_idx,
                             const int32_t* csc_ptr, const int32_t* csc_idx, hipStream_t stream, bool dq_only,
-                            int32_t* order_scratch, int onepass_keys, float* dq_acc) {
+                            int32_t* order_scratch, int onepass_keys, float* dq_acc, bool dkdv_only) {
     switch (d) {
-        case 64: return launch_bwd<64>(p, csr_ptr, csr_idx, csc_ptr, csc_idx, stream, dq_only, order_scratch, onepass_keys, dq_acc);
-        case 128: return launch_bwd<128>(p, csr_ptr, csr_idx, csc_ptr, csc_idx, stream, dq_only, order_scratch, onepass_keys, dq_acc);
-        case 256: return launch_bwd<256>(p, csr_ptr, csr_idx, csc_ptr, csc_idx, stream, dq_only, order_scratch, 0, nullptr);
+        case 64: return launch_bwd<64>(p, csr_ptr, csr_idx, csc_ptr, csc_idx, stream, dq_only, order_scratch, onepass_keys, dq_acc, dkdv_only);
+        case 128: return launch_bwd<128>(p, csr_ptr, csr_idx, csc_ptr, csc_idx, stream, dq_only, order_scratch, onepass_keys, dq_acc, dkdv_only);
+        case 256: return launch_bwd<256>(p, csr_ptr, csr_idx, csc_ptr, csc_idx, stream, dq_only, order_scratch, 0, nullptr, dkdv_only);
         default: return hipErrorInvalidValue;
     }
 }

@@ -210,7 +210,7 @@ __device__ __forceinline__ void load_tile_direct(const __bf16* base, long ld, in
         asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
                      :
                      : "s"(dst), "v"(base + (long)grow * ld + c * 8)
-                     : "memory");
+                     : "memory", "m0");
     }
 }
 __device__ __forceinline__ void wait_direct_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
@@ -258,7 +258,7 @@ struct TileLoader {
             asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
                          :
                          : "s"(dst), "v"(voff[u]), "s"(first_row)
-                         : "memory");
+                         : "memory", "m0");
         }
     }
     // copy instruction u of load() on its own, for callers that spread the copies over their MFMAs
@@ -266,7 +266,10 @@ struct TileLoader {
         const __bf16* first_row = uniform(first_row_in);
         const unsigned dst =
             __builtin_amdgcn_readfirstlane((unsigned)(size_t)(ATTN_LDS char*)tile) + lds0 + u * NW * 1024;
-        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(dst), "v"(voff[u]), "s"(first_row));
+        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+                     :
+                     : "s"(dst), "v"(voff[u]), "s"(first_row)
+                     : "memory", "m0");
     }
     // any tile: clamps rows at rows_valid - 1 when the tile reaches past the end
     __device__ __forceinline__ void load(const __bf16* base, long ld, int row_begin, int rows_valid, char* tile,

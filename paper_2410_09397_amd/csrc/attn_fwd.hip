@@ -251,13 +251,10 @@ template <int D>
 static hipError_t launch_fwd(const FusedParams& p, const int32_t* csr_ptr, const int32_t* csr_idx,
                              hipStream_t stream) {
     constexpr int lds = 2 * (2 * 64 * D * 2);
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fwd_kernel<D>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    // set on every call: the attribute belongs to the current device, and the call is cheap
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fwd_kernel<D>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
     FusedParams pf = p;
     pf.list_ptr = csr_ptr;
     pf.list_idx = csr_idx;

@@ -9,7 +9,8 @@ namespace attn {
 // Fused bf16 paths, d in {64, 128, 256}.  csr_* / csc_* are device pointers or nullptr (dense).
 hipError_t launch_fwd_fused(int d, const FusedParams& p, const int32_t* csr_ptr, const int32_t* csr_idx,
                             hipStream_t stream);
-// dq_only: run the query-owner kernel alone (dQ and delta), for callers that need neither dK nor dV.
+// dq_only: run the query-owner kernel alone (dQ and delta), for callers that need neither dK nor dV;
+// dkdv_only: run the key-owner kernel alone (it reads the delta an earlier call left in p.delta).
 // order_scratch: under a block mask, 3 * ceil(n / 128) int32 per mask of device scratch for the order in
 // which the workgroups take the blocks (longest list first), or nullptr (ascending order).
 // onepass_keys: 0 = the two-kernel tiling; 64 or 128 = the one-pass tiling with that many keys per
@@ -17,7 +18,7 @@ hipError_t launch_fwd_fused(int d, const FusedParams& p, const int32_t* csr_ptr,
 hipError_t launch_bwd_fused(int d, const FusedParams& p, const int32_t* csr_ptr, const int32_t* csr_idx,
                             const int32_t* csc_ptr, const int32_t* csc_idx, hipStream_t stream,
                             bool dq_only = false, int32_t* order_scratch = nullptr, int onepass_keys = 0,
-                            float* dq_acc = nullptr);
+                            float* dq_acc = nullptr, bool dkdv_only = false);
 // The three launches of the one-pass tiling (d = 64: key_block 64; d = 128: 64 or 128); p.list_*, p.order
 // describe the key-block columns of a block mask (or are null).
 hipError_t launch_bwd_onepass(int d, int key_block, const FusedParams& p, float* dq_acc, hipStream_t stream);
@@ -40,6 +41,7 @@ struct LargeDParams {
     float scale;
     int causal;
 };
+hipError_t configure_larged();  // kernel attributes; call before anything of a large-d call is launched
 hipError_t launch_larged(bool backward, const LargeDParams& p, hipStream_t stream);
 
 // Arguments of the generic fp32-arithmetic kernels (any n, d <= 512, any mask block edge).

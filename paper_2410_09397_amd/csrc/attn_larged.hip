@@ -410,17 +410,19 @@ static void run_gemm(const LargeDParams& p, const __bf16* A, const __bf16* B, __
 
 constexpr int kScoreLdsFwd = 3 * (256 + 128) * 32 * 2;      // 8 waves: three stages of a K and a Q chunk
 constexpr int kScoreLdsBwd = 2 * 2 * (128 + 128) * 32 * 2;  // 4 waves: two stages of K, Q, V, dO chunks
+// LDS sizes of the large-d kernels on the current device (set on every call: cheap, and per device).
+hipError_t configure_larged() {
+    hipError_t e = set_lds(reinterpret_cast<const void*>(ld_scores_kernel<kStats, 8>), kScoreLdsFwd);
+    if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_scores_kernel<kProbs, 8>), kScoreLdsFwd);
+    if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_scores_kernel<kBackward, 4>), kScoreLdsBwd);
+    if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_gemm_kernel<true>), kGemmLds);
+    if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_gemm_kernel<false>), kGemmLds);
+    return e;
+}
+
 hipError_t launch_larged(bool backward, const LargeDParams& p, hipStream_t stream) {
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = set_lds(reinterpret_cast<const void*>(ld_scores_kernel<kStats, 8>), kScoreLdsFwd);
-        if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_scores_kernel<kProbs, 8>), kScoreLdsFwd);
-        if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_scores_kernel<kBackward, 4>), kScoreLdsBwd);
-        if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_gemm_kernel<true>), kGemmLds);
-        if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_gemm_kernel<false>), kGemmLds);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    const hipError_t ce = configure_larged();
+    if (ce != hipSuccess) return ce;
     const unsigned bh = (unsigned)(p.batch * p.heads);
     const unsigned nbq = (unsigned)(p.npad / 128);
     const dim3 fgrid(nbq * (unsigned)(p.npad / 256) * bh), fblock(512);  // forward modes: 256-key tiles, 8 waves

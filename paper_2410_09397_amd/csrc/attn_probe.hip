@@ -82,13 +82,9 @@ attn_status attn_mfma_ceiling(int32_t iters, int32_t zero_operands, float* clock
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess) return ATTN_ERR_DEVICE;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return ATTN_ERR_DEVICE;
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(attn::mfma_ceiling_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, attn::kProbeLds) != hipSuccess)
-            return ATTN_ERR_DEVICE;
-        configured = true;
-    }
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(attn::mfma_ceiling_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, attn::kProbeLds) != hipSuccess)
+        return ATTN_ERR_DEVICE;
     const int blocks = attn::kProbeBlocksPerCu * cus;
     hipLaunchKernelGGL(attn::mfma_ceiling_kernel, dim3((unsigned)blocks), dim3(attn::kThreads), attn::kProbeLds,
                        static_cast<hipStream_t>(stream), clock_ghz, iters, zero_operands);

@@ -169,15 +169,13 @@ hipError_t run(const WgradParams& p, hipStream_t stream) {
     const int bh = p.batch * p.heads;
     const int blocks = (p.n + 127) / 128, chunks = wgrad_chunks(p.n);
     constexpr int proj_lds = D * D * 2, part_lds = 2 * 2 * 64 * D * 2;
-    static bool configured = false;
-    if (!configured) {
+    {  // set on every call: the attributes belong to the current device, and the calls are cheap
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(proj_kernel<D>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, proj_lds);
         if (e != hipSuccess) return e;
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_partial_kernel<D>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, part_lds);
         if (e != hipSuccess) return e;
-        configured = true;
     }
     hipLaunchKernelGGL(proj_kernel<D>, dim3((unsigned)(blocks * bh)), dim3(kThreads), proj_lds, stream, p.A1, p.X, p.Q,
                        p.n, bh);

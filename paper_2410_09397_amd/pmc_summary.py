@@ -6,20 +6,41 @@ Inputs are the CSV files of three profiler runs of the same bench command:
   --write DIR   rocprofv3 --pmc WRITE_SIZE         (with bench.py --calibrate-copy)
 The byte counters are scaled by what they read for the plain 1 GiB device copy that
 `--calibrate-copy` adds to the run.  Writes profiles/<kernel group>_<workload>.md and updates
-profiles/hbm_traffic.json (HBM bytes of one backward call), which bench.py reports as
-roofline.traffic.
+profiles/hbm_traffic.json (HBM bytes of one backward call, stamped with a hash of the kernel
+sources they were measured on), which bench.py reports as roofline.traffic and marks stale when
+the sources have changed since.
 """
 import argparse
 import collections
 import csv
 import glob
+import hashlib
 import json
 import os
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 COPY_BYTES = float(1 << 30)  # bytes read, and bytes written, by the calibration copy
 BWD_KERNELS = ("delta_kernel", "bwd_dkdv", "bwd_dq", "ld_scores_kernel<2,", "ld_gemm_kernel", "generic_delta",
-               "generic_dq", "generic_dkdv")
+               "generic_dq", "generic_dkdv", "block_len_kernel", "block_order_kernel", "bwd_prep_kernel",
+               "bwd_onepass_kernel")
+
+
+def source_hash():
+    """sha256 over the kernel sources and the C header (names and contents, sorted): what a stored
+    byte count was measured on."""
+    h = hashlib.sha256()
+    for d in (os.path.join(ROOT, "paper_2410_09397_amd", "csrc"), os.path.join(ROOT, "include")):
+        for name in sorted(os.listdir(d)):
+            path = os.path.join(d, name)
+            if os.path.isfile(path):
+                h.update(name.encode())
+                with open(path, "rb") as fh:
+                    h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def traffic_key(workload, tiling):
+    return workload if not tiling else "%s@tiling%d" % (workload, tiling)
 FWD_KERNELS = ("fwd_kernel", "ld_scores_kernel<0,", "ld_scores_kernel<1,", "ld_lse_combine", "generic_fwd")
 
 
@@ -73,6 +94,7 @@ def main():
     ap.add_argument("--workload-index", type=int, required=True)
     ap.add_argument("--shape", default=None, help="the --shape string given to bench.py, if any")
     ap.add_argument("--extra-frac", type=float, default=None, help="the --extra-frac given to bench.py, if any")
+    ap.add_argument("--tiling", type=int, default=0, help="the --tiling given to bench.py, if any")
     ap.add_argument("--stats", required=True)
     ap.add_argument("--fetch", required=True)
     ap.add_argument("--write", required=True)
@@ -95,14 +117,16 @@ def main():
     shape = (" --shape %s" % args.shape) if args.shape else ""
     if args.extra_frac is not None:
         shape += " --extra-frac %g" % args.extra_frac
+    if args.tiling:
+        shape += " --tiling %d" % args.tiling
     lines.append("# rocprofv3 summary: attention kernels, workload %s\n" % args.workload)
     lines.append("Commands (from the repository root, on one MI355X; `cd /tmp && export TMPDIR=/tmp` first):\n")
     lines.append("```")
     lines.append("rocprofv3 --kernel-trace --stats -d %s -o w%d --output-format csv -- python bench.py --workload %d%s "
-                 "--steps 5 --warmup 2 --no-cpu-baseline" % (args.stats, w, w, shape))
+                 "--steps 5 --warmup 2 --sustain 0 --no-cpu-baseline" % (args.stats, w, w, shape))
     for c, d in (("FETCH_SIZE", args.fetch), ("WRITE_SIZE", args.write)):
         lines.append("rocprofv3 --pmc %s -d %s -o pmc --output-format csv -- python bench.py --workload %d%s --steps 3 "
-                     "--warmup 1 --no-cpu-baseline --calibrate-copy" % (c, d, w, shape))
+                     "--warmup 1 --sustain 0 --no-cpu-baseline --calibrate-copy" % (c, d, w, shape))
     lines.append("python -m paper_2410_09397_amd.pmc_summary --workload %s --workload-index %d%s --stats %s --fetch %s "
                  "--write %s" % (args.workload, w, shape, args.stats, args.fetch, args.write))
     lines.append("```\n")
@@ -151,11 +175,14 @@ def main():
                                                            wl.bwd_flops() / (tot["bwd"][0] * 1e-9) * 1e-12 / 25.0))
     out_dir = os.path.join(ROOT, "profiles")
     os.makedirs(out_dir, exist_ok=True)
-    with open(os.path.join(out_dir, "attn_kernels_%s.md" % args.workload), "w") as fh:
+    key = traffic_key(args.workload, args.tiling)
+    lines.append("Kernel sources: hash %s (paper_2410_09397_amd.pmc_summary.source_hash)." % source_hash())
+    with open(os.path.join(out_dir, "attn_kernels_%s.md" % key.replace("@", "_")), "w") as fh:
         fh.write("\n".join(lines) + "\n")
     tpath = os.path.join(out_dir, "hbm_traffic.json")
     traffic = json.load(open(tpath)) if os.path.exists(tpath) else {}
-    traffic[args.workload] = bwd_bytes
+    traffic[key] = {"bytes": bwd_bytes, "read": tot["bwd"][1], "written": tot["bwd"][2], "bwd_ms_summed": tot["bwd"][0] / 1e6,
+                    "source_hash": source_hash()}
     with open(tpath, "w") as fh:
         json.dump(traffic, fh, indent=1, sort_keys=True)
     print("\n".join(lines))

@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 
 from paper_2410_09397_amd import synth
-from tests.helpers import LSE_TOL, TOL, oracle_reference, rel_err, to_dev, to_np
+from tests.helpers import LSE_TOL, TOL, check, oracle_reference, rel_err, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -89,19 +89,19 @@ def test_forward_and_backward_match_oracle(w):
     tol, ltol = TOL[w.dtype], LSE_TOL[w.dtype]
 
     O, LSE = attn.attn_fwd(Q, K, V, w.scale, causal=w.causal, mask=mask)
-    assert rel_err(to_np(O), ref["O"]) <= tol
+    check(w.name, "O", to_np(O), ref["O"], w.dtype)
     assert np.abs(to_np(LSE) - ref["LSE"]).max() <= ltol * max(1.0, np.abs(ref["LSE"]).max())
 
     # backward in isolation: both sides consume the same rounded O and fp32 LSE
     O_in, LSE_in = to_dev(ref["O_in"], w.dtype), to_dev(ref["LSE_in"], "f32")
     grads = gpu_bwd(w, mask, Q, K, V, O_in, dO, LSE_in)
     for name, g, r in zip(("dQ", "dK", "dV"), grads, ref["iso"]):
-        assert rel_err(to_np(g), r) <= tol, name
+        check(w.name + " isolated", name, to_np(g), r, w.dtype)
 
     # chained after the GPU forward, against the oracle's exact chain
     grads = gpu_bwd(w, mask, Q, K, V, O, dO, LSE)
     for name, g, r in zip(("dQ", "dK", "dV"), grads, ref["exact"]):
-        assert rel_err(to_np(g), r) <= tol, name
+        check(w.name + " chained", name, to_np(g), r, w.dtype, chained=True)
 
 
 def _run_all(w, inp, keep, causal):
@@ -171,11 +171,14 @@ def test_backward_is_deterministic():
         assert torch.equal(x, y)
 
 
-def test_strided_layout_matches_contiguous():
-    """[batch, n, heads, d] storage viewed as [batch, heads, n, d] gives the same bits."""
+@pytest.mark.parametrize("d,dtype,n", [(64, "bf16", 300), (128, "bf16", 300), (256, "bf16", 200), (512, "bf16", 300),
+                                       (96, "bf16", 150), (40, "f32", 150)])
+def test_strided_layout_matches_contiguous(d, dtype, n):
+    """[batch, n, heads, d] storage viewed as [batch, heads, n, d] gives the same bits, on every path:
+    fused (d = 64, 128, 256), four-phase (512) and the generic fp32-FMA kernels (bf16 d = 96, fp32)."""
     import torch
     from paper_2410_09397_amd import attn
-    w = W("strided", 63, 2, 3, 300, 64, "bf16", causal=True)
+    w = W("strided", 63, 2, 3, n, d, dtype, causal=True)
     inp = synth.make_inputs(w)
     cont = [to_dev(inp[t], w.dtype) for t in ("Q", "K", "V", "dO")]
     perm = [t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for t in cont]
@@ -189,6 +192,33 @@ def test_strided_layout_matches_contiguous():
     outs = tuple(torch.empty_like(perm[0]) for _ in range(3))
     attn.attn_bwd(*perm[:3], Op, perm[3], Lp, w.scale, causal=True, out=outs)
     for a, b in zip(gc, outs):
+        assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("d,dtype", [(128, "bf16"), (512, "bf16"), (48, "f32")])
+def test_call_on_a_non_default_stream(d, dtype):
+    """Everything a call launches goes to the stream it is given: run on a side stream (default
+    priority) while the current stream holds other work, the results equal those of the current stream."""
+    import torch
+    from paper_2410_09397_amd import attn
+    w = W("stream", 66, 1, 2, 700, d, dtype, causal=True)
+    inp = synth.make_inputs(w)
+    Q, K, V, dO = (to_dev(inp[t], w.dtype) for t in ("Q", "K", "V", "dO"))
+    O0, L0 = attn.attn_fwd(Q, K, V, w.scale, causal=True)
+    g0 = attn.attn_bwd(Q, K, V, O0, dO, L0, w.scale, causal=True)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    filler = torch.randn(2048, 2048, device="cuda")
+    for _ in range(4):
+        filler = filler @ filler * 1e-3  # keeps the current stream busy meanwhile
+    O1, L1 = torch.empty_like(O0), torch.empty_like(L0)
+    g1 = tuple(torch.empty_like(Q) for _ in range(3))
+    attn.attn_fwd(Q, K, V, w.scale, causal=True, stream=side, out=(O1, L1))
+    attn.attn_bwd(Q, K, V, O1, dO, L1, w.scale, causal=True, stream=side, out=g1)
+    side.synchronize()
+    torch.cuda.synchronize()
+    assert torch.equal(O0, O1) and torch.equal(L0, L1)
+    for a, b in zip(g0, g1):
         assert torch.equal(a, b)
 
 
@@ -214,3 +244,15 @@ def test_empty_and_fully_masked_rows():
     assert rel_err(to_np(O), rO) <= TOL["bf16"]
     for g, r in zip((dQ, dK, dV), rg):
         assert rel_err(to_np(g), r) <= TOL["bf16"]
+
+    # the same on the generic fp32 kernels (block edge 16): rows 16..31 keep nothing
+    w = W("emptyrow_generic", 67, 1, 2, 48, 24, "f32", block=16)
+    inp = synth.make_inputs(w)
+    O, LSE, dQ, dK, dV = _run_all(w, inp, keep, False)
+    assert torch.all(O[:, :, 16:32] == 0) and torch.all(torch.isneginf(LSE[:, :, 16:32]))
+    assert torch.all(dQ[:, :, 16:32] == 0)
+    rO, rL = orc.attn_fwd(inp["Q"], inp["K"], inp["V"], w.scale, keep=keep, block=16)
+    rg = orc.attn_bwd(inp["Q"], inp["K"], inp["V"], rO, inp["dO"], rL, w.scale, keep=keep, block=16)
+    assert rel_err(to_np(O), rO) <= TOL["f32"]
+    for g, r in zip((dQ, dK, dV), rg):
+        assert rel_err(to_np(g), r) <= TOL["f32"]

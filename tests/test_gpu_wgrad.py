@@ -44,7 +44,7 @@ def test_wgrad_matches_the_papers_algorithm(n, d, heads):
     g = _run_gpu(w, inp, 1.0, False)
     assert g.shape == (1, heads, d, d)
     for h in range(heads):
-        ref, _, _, _ = orc.alg1_wgrad(inp["A1"][0, h], inp["A2"][0, h], inp["A3"][0, h], inp["dO"][0, h],
+        ref, _, _, _ = orc.wgrad(inp["A1"][0, h], inp["A2"][0, h], inp["A3"][0, h], inp["dO"][0, h],
                                       inp["X"][0, h], inp["Y"][0, h])
         assert helpers.rel_err(g[0, h], ref) <= TOL
 

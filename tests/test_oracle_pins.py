@@ -63,11 +63,11 @@ def test_backward_matches_central_differences_of_forward(mask):
 # ------------------------------------------------------- the paper's own gradient (Def. 3.2)
 def test_paper_weight_gradient_equals_A1T_dQ_and_finite_differences():
     """With Q = A_1 X, K = A_2, V = A_3 Y and scale 1, dL/dX = A_1^T p A_2 = A_1^T dQ.
-    The no-cache algorithm is evaluated by separate oracle code (no LSE, no shift)."""
+    g is evaluated by separate oracle code written from Def. 3.2 (no LSE, no shift)."""
     n, d = 7, 3
     A1, A2, A3, dO = (rand(n, d, std=0.6) for _ in range(4))
     X, Y = rand(d, d, std=0.6), rand(d, d, std=0.6)
-    g, f, q, p = orc.alg1_wgrad(A1, A2, A3, dO, X, Y)
+    g, f, q, p = orc.wgrad(A1, A2, A3, dO, X, Y)
     Q, K, V = (A1 @ X)[None, None], A2[None, None], (A3 @ Y)[None, None]
     O, LSE = orc.attn_fwd(Q, K, V, 1.0)
     dQ, dK, dV, f2, q2, p2 = orc.attn_bwd_head(Q[0, 0], K[0, 0], V[0, 0], O[0, 0], dO, LSE[0, 0], 1.0)
@@ -93,6 +93,44 @@ def test_paper_weight_gradient_equals_A1T_dQ_and_finite_differences():
         numY[idx] = (loss(Q, K, (A3 @ Yp)[None, None], dO[None, None], 1.0)
                      - loss(Q, K, (A3 @ Ym)[None, None], dO[None, None], 1.0)) / (2 * eps)
     assert np.abs(numY - A3.T @ dV).max() < 1e-8
+
+
+# ------------------------------------------------- the four-phase small-cache scheme (App. C)
+@pytest.mark.parametrize("n,d,B", [(7, 3, 1), (7, 3, 2), (8, 4, 2), (8, 4, 4), (9, 5, 3), (6, 6, 16), (10, 4, 7)])
+def test_small_cache_scheme_computes_the_same_gradient(n, d, B):
+    """Four phases over B x B blocks, every n x n intermediate through memory, give the g of
+    Def. 3.2 (App. C: "calculates the same gradients"), for block edges that divide n and d,
+    that do not, and that exceed both."""
+    A1, A2, A3, dO = (rand(n, d, std=0.6) for _ in range(4))
+    X, Y = rand(d, d, std=0.6), rand(d, d, std=0.6)
+    g, _, _, _ = orc.wgrad(A1, A2, A3, dO, X, Y)
+    gb, rd, wr = orc.small_cache_wgrad(A1, A2, A3, dO, X, Y, B)
+    assert np.allclose(gb, g, rtol=1e-11, atol=1e-13)
+    assert rd > 0 and wr > 0
+
+
+@pytest.mark.parametrize("n,d,B", [(8, 4, 2), (12, 6, 3), (16, 8, 4), (16, 16, 8)])
+def test_small_cache_scheme_moves_what_its_lemmas_count(n, d, B):
+    """Element transfers of the replayed schedule against the count of its own block loops (B | n,
+    B | d): every block product reads two B x B blocks per k-step and writes its block once; the
+    elementwise passes read and write n x n.  With B = sqrt(M / 4) the total is
+    12 (n^2 d + n d^2) / sqrt(M) + O(n^2): the O((n^2 d + n d^2) / sqrt(M)) of Thm 4.3."""
+    A1, A2, A3, dO = (rand(n, d, std=0.4) for _ in range(4))
+    X, Y = rand(d, d, std=0.4), rand(d, d, std=0.4)
+    _, rd, wr = orc.small_cache_wgrad(A1, A2, A3, dO, X, Y, B)
+    nb, db = n // B, d // B
+    prod = lambda mb, nb_, kb: 2 * B * B * mb * nb_ * kb  # operand reads of one blocked product
+    reads = (2 * prod(nb, db, db)      # S = A_1 X, h = A_3 Y
+             + 2 * prod(nb, nb, db)    # S A_2^T, dO h^T
+             + prod(db, nb, nb)        # T = A_1^T p
+             + prod(db, db, nb)        # g = T A_2
+             + n * n + (n * n + n)     # exp / row-sum pass; normalisation pass (reads l)
+             + 4 * n * n)              # phase 3: f and q twice
+    writes = 2 * n * d + 2 * n * n + (n * n + n) + n * n + n * n + d * n + d * d
+    assert rd == reads and wr == writes
+    M = 4 * B * B
+    lead = 12 * (n * n * d + n * d * d) / np.sqrt(M)
+    assert abs(rd - (lead + 6 * n * n + n)) < 1e-9
 
 
 # ----------------------------------------------------------------------------- invariants
