@@ -88,9 +88,12 @@ def main():
                     help="block-sparse workload only: share of non-diagonal key blocks kept per query-block row")
     ap.add_argument("--tiling", type=int, default=0,
                     help="attn_bwd_tiling of include/attn_mi355x.h (0 = the library's choice, 1 = two kernels, "
-                         "2 / 3 = one pass with 64 / 128 keys per workgroup)")
+                         "2 / 3 = one pass with 64 / 128 keys per workgroup, 6 = four-phase scheme, 7 = fused split-d)")
     ap.add_argument("--sustain", type=float, default=1.0,
                     help="seconds of back-to-back steps after the timed ones for the `sustained` figure (0 = none)")
+    ap.add_argument("--no-kernel-split", action="store_true",
+                    help="do not time the two kernels of the two-kernel tiling one at a time (profiling runs: "
+                         "every launch of the run then belongs to a whole step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--wgrad", action="store_true",
                     help="also time attn_bwd_wgrad (the paper's weight gradient) on the same shape and "
@@ -179,7 +182,8 @@ def main():
 
     # the two kernels of the two-kernel tiling one at a time (the library runs one of them alone on request)
     kernels = None
-    if w.dtype == "bf16" and w.d in (64, 128, 256) and args.tiling in (0, 1) and (not w.sparse or w.block == 128):
+    if (not args.no_kernel_split and w.dtype == "bf16" and w.d in (64, 128, 256) and args.tiling in (0, 1)
+            and (not w.sparse or w.block == 128)):
         kernels = []
         pairs = w.batch * w.heads * float(w.n) * w.n * w.kept_fraction()  # visible (query, key) pairs
         for name, part, mults in (("bwd_dq_kernel (+ delta)", attn.ATTN_BWD_PART_DQ, 6), ("bwd_dkdv_kernel", attn.ATTN_BWD_PART_DKDV, 8)):

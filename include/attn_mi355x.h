@@ -55,7 +55,7 @@ typedef enum {
 typedef enum { ATTN_F32 = 0, ATTN_BF16 = 1 } attn_dtype;
 
 /*
- * Tilings of the fused bf16 backward (d in {64, 128, 256}).  All compute the same gradients; they
+ * Tilings of the bf16 backward.  All compute the same gradients; they
  * differ in which block stays on chip, i.e. in the cache size M they need and in the traffic they
  * cause (the trade-off of Thm 1.1 / Sec. 4), and exist side by side so that it can be measured.
  *   ATTN_BWD_AUTO          the library's choice (the fastest measured for the shape)
@@ -72,7 +72,14 @@ typedef enum { ATTN_F32 = 0, ATTN_BF16 = 1 } attn_dtype;
  *                          workspace) and leaves dK, dV untouched; PART_DKDV writes dK, dV, leaves dQ
  *                          untouched and reads the v (and, under a block mask, nothing else) that an
  *                          earlier TWO_KERNEL or PART_DQ call left in the same workspace
- * A tiling that does not exist for the shape gives ATTN_ERR_UNSUPPORTED; other paths ignore it.
+ *   ATTN_BWD_FOUR_PHASE    the four-phase small-cache scheme of App. C (f and p through the workspace) at
+ *                          a head dimension where the fused kernels are the default: d in {128, 256}
+ *                          (it is what d in {512, 1024} run anyway); no block mask, n <= 32768
+ *   ATTN_BWD_SPLIT_D       fused kernels whose owned block is 32 rows with the contraction over d split
+ *                          over the waves of a workgroup: the fused alternative where the four-phase
+ *                          scheme is the default, d = 512 (also d = 256); no block mask; bit-reproducible
+ * A tiling that does not exist for the shape gives ATTN_ERR_UNSUPPORTED; the generic fp32 kernels
+ * ignore the field, and so does the forward.
  */
 typedef enum {
     ATTN_BWD_AUTO = 0,
@@ -80,7 +87,9 @@ typedef enum {
     ATTN_BWD_ONEPASS_K64 = 2,
     ATTN_BWD_ONEPASS_K128 = 3,
     ATTN_BWD_PART_DQ = 4,
-    ATTN_BWD_PART_DKDV = 5
+    ATTN_BWD_PART_DKDV = 5,
+    ATTN_BWD_FOUR_PHASE = 6,
+    ATTN_BWD_SPLIT_D = 7
 } attn_bwd_tiling;
 
 typedef struct {

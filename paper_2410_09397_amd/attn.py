@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libattn_mi355x.so")
 ATTN_OK, ATTN_ERR_INVALID_ARG, ATTN_ERR_UNSUPPORTED, ATTN_ERR_WORKSPACE, ATTN_ERR_DEVICE = range(5)
 ATTN_F32, ATTN_BF16 = 0, 1
 (ATTN_BWD_AUTO, ATTN_BWD_TWO_KERNEL, ATTN_BWD_ONEPASS_K64, ATTN_BWD_ONEPASS_K128, ATTN_BWD_PART_DQ,
- ATTN_BWD_PART_DKDV) = range(6)
+ ATTN_BWD_PART_DKDV, ATTN_BWD_FOUR_PHASE, ATTN_BWD_SPLIT_D) = range(8)
 
 EXPORTS = ("attn_workspace_bytes", "attn_fwd", "attn_bwd", "attn_bwd_noalloc", "attn_bwd_blocksparse",
            "attn_wgrad_workspace_bytes", "attn_bwd_wgrad", "attn_blockmask_validate", "attn_mfma_ceiling",

@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libattn_mi355x.so")
-SOURCES = ["attn_api.hip", "attn_fwd.hip", "attn_bwd.hip", "attn_bwd_onepass.hip", "attn_generic.hip", "attn_larged.hip", "attn_wgrad.hip",
+SOURCES = ["attn_api.hip", "attn_fwd.hip", "attn_bwd.hip", "attn_bwd_onepass.hip", "attn_generic.hip", "attn_larged.hip", "attn_splitd.hip", "attn_wgrad.hip",
            "attn_probe.hip"]
 # -packed-fp32-ops is switched off: packed fp32 VALU forms are not trusted on this target.
 # -Wno-inline-asm: the tile copies write M0 in inline assembly and say so in their clobber lists; clang notes that

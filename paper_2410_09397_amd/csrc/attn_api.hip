@@ -19,7 +19,7 @@ using attn::FusedParams;
 using attn::GenericParams;
 using attn::LargeDParams;
 
-enum class Path { kFused, kLargeD, kGeneric };
+enum class Path { kFused, kLargeD, kGeneric, kSplitD, kNone };
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -38,7 +38,7 @@ attn_status check_desc(const attn_desc* d) {
         return ATTN_ERR_INVALID_ARG;
     // the tile copies address a tile's rows with 32-bit byte offsets from its first row
     if (d->stride_n >= (int64_t)1 << 22) return ATTN_ERR_UNSUPPORTED;
-    if (d->bwd_tiling < ATTN_BWD_AUTO || d->bwd_tiling > ATTN_BWD_PART_DKDV) return ATTN_ERR_INVALID_ARG;
+    if (d->bwd_tiling < ATTN_BWD_AUTO || d->bwd_tiling > ATTN_BWD_SPLIT_D) return ATTN_ERR_INVALID_ARG;
     return ATTN_OK;
 }
 
@@ -77,8 +77,20 @@ bool is_onepass(int tiling) { return tiling == ATTN_BWD_ONEPASS_K64 || tiling ==
 
 // d = 1024 exists on the large-d path only (the generic kernels stop at 512).
 attn_status check_path(const attn_desc* d, const attn_blockmask* m) {
-    if (pick_path(d, m) == Path::kFused && pick_tiling(d) == 0) return ATTN_ERR_UNSUPPORTED;
     return (d->d > 512 && pick_path(d, m) != Path::kLargeD) ? ATTN_ERR_UNSUPPORTED : ATTN_OK;
+}
+
+// The path of the backward: the caller can ask for the four-phase scheme at head dimensions where the
+// fused kernels are the default, and for the fused split-d kernels where the four-phase scheme is.
+Path bwd_path(const attn_desc* d, const attn_blockmask* m) {
+    const bool plain = d->dtype == ATTN_BF16 && !m;
+    if (d->bwd_tiling == ATTN_BWD_FOUR_PHASE)
+        return plain && d->n <= 32768 && (d->d == 128 || d->d == 256 || d->d == 512 || d->d == 1024) ? Path::kLargeD
+                                                                                                       : Path::kNone;
+    if (d->bwd_tiling == ATTN_BWD_SPLIT_D) return plain && (d->d == 256 || d->d == 512) ? Path::kSplitD : Path::kNone;
+    if (check_path(d, m) != ATTN_OK) return Path::kNone;
+    const Path path = pick_path(d, m);
+    return (path == Path::kFused && pick_tiling(d) == 0) ? Path::kNone : path;
 }
 
 size_t delta_bytes(const attn_desc* d) { return round_up((size_t)d->batch * d->heads * d->n * sizeof(float), 256); }
@@ -164,8 +176,8 @@ attn_status bwd_impl(const attn_desc* desc, const attn_blockmask* mask, const vo
     if (st != ATTN_OK) return st;
     st = check_mask(desc, mask);
     if (st != ATTN_OK) return st;
-    st = check_path(desc, mask);
-    if (st != ATTN_OK) return st;
+    const Path path = bwd_path(desc, mask);
+    if (path == Path::kNone) return ATTN_ERR_UNSUPPORTED;
     if (is_empty(desc)) return ATTN_OK;
     if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV) return ATTN_ERR_INVALID_ARG;
     if (desc->dtype == ATTN_BF16 && !(aligned16(Q) && aligned16(K) && aligned16(V) && aligned16(O) &&
@@ -175,7 +187,22 @@ attn_status bwd_impl(const attn_desc* desc, const attn_blockmask* mask, const vo
     if (!workspace || workspace_bytes < need || !aligned16(workspace)) return ATTN_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e;
-    switch (pick_path(desc, mask)) {
+    switch (path) {
+        case Path::kSplitD: {
+            FusedParams p = fused_params(desc);
+            p.Q = static_cast<const __bf16*>(Q);
+            p.K = static_cast<const __bf16*>(K);
+            p.V = static_cast<const __bf16*>(V);
+            p.O = static_cast<const __bf16*>(O);
+            p.dO = static_cast<const __bf16*>(dO);
+            p.dQ = static_cast<__bf16*>(dQ);
+            p.dK = static_cast<__bf16*>(dK);
+            p.dV = static_cast<__bf16*>(dV);
+            p.LSE = LSE;
+            p.delta = static_cast<float*>(workspace);
+            e = attn::launch_bwd_splitd(desc->d, p, s);
+            break;
+        }
         case Path::kFused: {
             FusedParams p = fused_params(desc);
             p.Q = static_cast<const __bf16*>(Q);
@@ -303,13 +330,16 @@ extern "C" {
 size_t attn_workspace_bytes(const attn_desc* desc, const attn_blockmask* mask) {
     if (check_desc(desc) != ATTN_OK || check_mask(desc, mask) != ATTN_OK || check_path(desc, mask) != ATTN_OK) return 0;
     if (is_empty(desc)) return 256;
-    if (pick_path(desc, mask) == Path::kLargeD) {
-        const size_t bwd = delta_bytes(desc) + 2 * nn_bytes(desc);
-        const size_t fwd = 2 * stat_bytes(desc) + nn_bytes(desc);
-        return bwd > fwd ? bwd : fwd;
+    // the forward goes by d alone; the backward also by the tiling asked for (one that does not exist
+    // for the shape is refused by the backward itself and needs nothing here)
+    const size_t fwd = pick_path(desc, mask) == Path::kLargeD ? 2 * stat_bytes(desc) + nn_bytes(desc) : 0;
+    size_t bwd = delta_bytes(desc);
+    switch (bwd_path(desc, mask)) {
+        case Path::kLargeD: bwd = delta_bytes(desc) + 2 * nn_bytes(desc); break;
+        case Path::kFused: bwd = fused_bytes(desc, mask); break;
+        default: break;
     }
-    if (pick_path(desc, mask) == Path::kFused) return fused_bytes(desc, mask);
-    return delta_bytes(desc);
+    return bwd > fwd ? bwd : fwd;
 }
 
 attn_status attn_fwd(const attn_desc* desc, const attn_blockmask* mask, const void* Q, const void* K,
@@ -325,8 +355,9 @@ attn_status attn_fwd(const attn_desc* desc, const attn_blockmask* mask, const vo
     if (desc->dtype == ATTN_BF16 && !(aligned16(Q) && aligned16(K) && aligned16(V) && aligned16(O)))
         return ATTN_ERR_INVALID_ARG;
     const Path path = pick_path(desc, mask);
+    // the forward's own share of attn_workspace_bytes: row statistics and the matrix f
     if (path == Path::kLargeD &&
-        (!workspace || workspace_bytes < attn_workspace_bytes(desc, mask) || !aligned16(workspace)))
+        (!workspace || workspace_bytes < 2 * stat_bytes(desc) + nn_bytes(desc) || !aligned16(workspace)))
         return ATTN_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e;
@@ -380,8 +411,7 @@ attn_status attn_bwd_noalloc(const attn_desc* desc, const void* Q, const void* K
                              const void* dO, const float* LSE, void* dQ, void* dK, void* dV, void* stream) {
     attn_status st = check_desc(desc);
     if (st != ATTN_OK) return st;
-    st = check_path(desc, nullptr);
-    if (st != ATTN_OK) return st;
+    if (bwd_path(desc, nullptr) == Path::kNone) return ATTN_ERR_UNSUPPORTED;
     if (is_empty(desc)) return ATTN_OK;
     if (attn_workspace_bytes(desc, nullptr) > (size_t)ATTN_NOALLOC_SCRATCH_BYTES) return ATTN_ERR_WORKSPACE;
     void* ptr = nullptr;

@@ -23,6 +23,9 @@ hipError_t launch_bwd_fused(int d, const FusedParams& p, const int32_t* csr_ptr,
 // describe the key-block columns of a block mask (or are null).
 hipError_t launch_bwd_onepass(int d, int key_block, const FusedParams& p, float* dq_acc, hipStream_t stream);
 
+// Fused split-d backward (bf16, d in {256, 512}, no block mask): delta kernel, query-owner and key-owner launches.
+hipError_t launch_bwd_splitd(int d, const FusedParams& p, hipStream_t stream);
+
 // delta[b, h, i] = sum_k dO_ik O_ik for bf16 tensors (p.O, p.dO, p.delta), any d % 8 == 0.
 void launch_delta(const FusedParams& p, int d, hipStream_t stream);
 

@@ -22,7 +22,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 COPY_BYTES = float(1 << 30)  # bytes read, and bytes written, by the calibration copy
 BWD_KERNELS = ("delta_kernel", "bwd_dkdv", "bwd_dq", "ld_scores_kernel<2,", "ld_gemm_kernel", "generic_delta",
                "generic_dq", "generic_dkdv", "block_len_kernel", "block_order_kernel", "bwd_prep_kernel",
-               "bwd_onepass_kernel")
+               "bwd_onepass_kernel", "bwd_splitd_kernel")
 
 
 def source_hash():
@@ -76,10 +76,10 @@ def counter_avg(d, counter):
     return {k: (sum(v) / COPIES if "copyBuffer" in k else sum(v) / len(v)) for k, v in acc.items()}
 
 
-def per_call_weights(name, calls, base_calls):
+def per_call_weights(name, calls, base_calls, four_phase_bwd=True):
     """(launches per attn_bwd call, launches per attn_fwd call) of a kernel."""
-    if "ld_gemm_kernel<false>" in name:  # dQ = dS K in the backward, O = P V in the forward
-        return 1.0, 1.0
+    if "ld_gemm_kernel<false>" in name:  # dQ = dS K in the four-phase backward, O = P V in the large-d forward
+        return (1.0, 1.0) if four_phase_bwd else (0.0, calls / float(base_calls))
     k = calls / float(base_calls)
     return (k, 0.0) if is_in(name, BWD_KERNELS) else (0.0, k)
 
@@ -99,6 +99,8 @@ def main():
     ap.add_argument("--fetch", required=True)
     ap.add_argument("--write", required=True)
     ap.add_argument("--bench-json", default=None, help="file holding the bench.py JSON line of the stats run")
+    ap.add_argument("--line-only", action="store_true",
+                    help="print one line (time, bytes read and written by one attn_bwd call) and write no file: sweeps")
     args = ap.parse_args()
 
     stats = kernel_stats(args.stats)
@@ -123,10 +125,10 @@ def main():
     lines.append("Commands (from the repository root, on one MI355X; `cd /tmp && export TMPDIR=/tmp` first):\n")
     lines.append("```")
     lines.append("rocprofv3 --kernel-trace --stats -d %s -o w%d --output-format csv -- python bench.py --workload %d%s "
-                 "--steps 5 --warmup 2 --sustain 0 --no-cpu-baseline" % (args.stats, w, w, shape))
+                 "--steps 5 --warmup 2 --sustain 0 --no-kernel-split --no-cpu-baseline" % (args.stats, w, w, shape))
     for c, d in (("FETCH_SIZE", args.fetch), ("WRITE_SIZE", args.write)):
         lines.append("rocprofv3 --pmc %s -d %s -o pmc --output-format csv -- python bench.py --workload %d%s --steps 3 "
-                     "--warmup 1 --sustain 0 --no-cpu-baseline --calibrate-copy" % (c, d, w, shape))
+                     "--warmup 1 --sustain 0 --no-kernel-split --no-cpu-baseline --calibrate-copy" % (c, d, w, shape))
     lines.append("python -m paper_2410_09397_amd.pmc_summary --workload %s --workload-index %d%s --stats %s --fetch %s "
                  "--write %s" % (args.workload, w, shape, args.stats, args.fetch, args.write))
     lines.append("```\n")
@@ -149,7 +151,7 @@ def main():
         rd = fetch.get(name, 0.0) * f_r * 1024.0
         wr = write.get(name, 0.0) * f_w * 1024.0
         # a kernel launched more than once per call (the large-d GEMM) counts that many times
-        wb, wf = per_call_weights(name, calls, base_calls)
+        wb, wf = per_call_weights(name, calls, base_calls, any("ld_scores_kernel<2," in n for n in stats))
         for grp, k in (("bwd", wb), ("fwd", wf)):
             tot[grp][0] += avg * k
             tot[grp][1] += rd * k
@@ -175,6 +177,11 @@ def main():
                                                            wl.bwd_flops() / (tot["bwd"][0] * 1e-9) * 1e-12 / 25.0))
     out_dir = os.path.join(ROOT, "profiles")
     os.makedirs(out_dir, exist_ok=True)
+    if args.line_only:
+        print("%s tiling %d: attn_bwd %.3f ms, HBM read %.1f MB, written %.1f MB, total %.1f MB = %.2f x yardstick %.1f MB"
+              % (args.workload, args.tiling, tot["bwd"][0] / 1e6, tot["bwd"][1] / 1e6, tot["bwd"][2] / 1e6, bwd_bytes / 1e6,
+                 bwd_bytes / y, y / 1e6))
+        return
     key = traffic_key(args.workload, args.tiling)
     lines.append("Kernel sources: hash %s (paper_2410_09397_amd.pmc_summary.source_hash)." % source_hash())
     with open(os.path.join(out_dir, "attn_kernels_%s.md" % key.replace("@", "_")), "w") as fh:

@@ -8,7 +8,7 @@ from tests.helpers import TOL, check, oracle_reference, rel_err, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
 
-TWO_KERNEL, ONEPASS_K64, ONEPASS_K128 = 1, 2, 3
+TWO_KERNEL, ONEPASS_K64, ONEPASS_K128, FOUR_PHASE, SPLIT_D = 1, 2, 3, 6, 7
 
 
 def W(name, index, b, h, n, d, dtype="bf16", **kw):
@@ -70,6 +70,35 @@ def test_one_pass_tilings_match_oracle(w):
         assert np.abs(a - b).max() <= 2e-2 * max(np.abs(b).max(), 1e-3)
 
 
+OTHER_PATH = [
+    # the four-phase scheme where the fused kernels are the default, the fused split-d kernels where it is
+    (W("t4_d128_causal", 171, 1, 2, 512, 128, causal=True, dO_std=0.1), FOUR_PHASE),
+    (W("t4_d256_ragged", 172, 1, 2, 333, 256), FOUR_PHASE),
+    (W("t7_d512", 173, 1, 2, 384, 512), SPLIT_D),
+    (W("t7_d512_ragged_causal", 174, 2, 1, 333, 512, causal=True), SPLIT_D),
+    (W("t7_d512_one_row", 175, 1, 1, 1, 512, causal=True), SPLIT_D),
+    (W("t7_d512_33_rows", 176, 1, 2, 33, 512), SPLIT_D),
+    (W("t7_d256_causal", 177, 1, 2, 700, 256, causal=True), SPLIT_D),
+]
+
+
+@pytest.mark.parametrize("w,tiling", OTHER_PATH, ids=lambda x: x.name if hasattr(x, "name") else str(x))
+def test_other_path_tilings_match_oracle(w, tiling):
+    import torch
+    print("case", w, "tiling", tiling, flush=True)
+    inp = synth.make_inputs(w)
+    ref = oracle_reference(w, inp)
+    Q, K, V, dO = (to_dev(inp[t], w.dtype) for t in ("Q", "K", "V", "dO"))
+    O_in, LSE_in = to_dev(ref["O_in"], w.dtype), to_dev(ref["LSE_in"], "f32")
+    grads = run_bwd(w, None, tiling, Q, K, V, O_in, dO, LSE_in)
+    torch.cuda.synchronize()
+    for name, g, r in zip(("dQ", "dK", "dV"), grads, ref["iso"]):
+        check("%s tiling %d" % (w.name, tiling), name, to_np(g), r, w.dtype)
+    again = run_bwd(w, None, tiling, Q, K, V, O_in, dO, LSE_in)
+    for a, b in zip(grads, again):
+        assert torch.equal(a, b), tiling  # neither path has atomics
+
+
 def test_unsupported_tilings_are_rejected():
     import torch
     from paper_2410_09397_amd import attn
@@ -78,4 +107,9 @@ def test_unsupported_tilings_are_rejected():
     for tiling in (ONEPASS_K64, ONEPASS_K128):
         with pytest.raises(attn.AttnError) as e:
             attn.attn_bwd(x, x, x, x, x, lse, 1.0, tiling=tiling)
+        assert e.value.status == attn.ATTN_ERR_UNSUPPORTED
+    x64 = torch.zeros(1, 1, 128, 64, dtype=torch.bfloat16, device="cuda")
+    for tiling in (FOUR_PHASE, SPLIT_D):
+        with pytest.raises(attn.AttnError) as e:
+            attn.attn_bwd(x64, x64, x64, x64, x64, lse, 1.0, tiling=tiling)
         assert e.value.status == attn.ATTN_ERR_UNSUPPORTED
