@@ -112,7 +112,7 @@ def main():
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
 
     import torch
-    from paper_2410_09397_amd import attn, io_bound, synth
+    from paper_2410_09397_amd import attn, io_bound, pmc_summary, synth
     if args.mfma_ceiling:
         print(json.dumps({"probe": "mfma_ceiling", "unit": "TFLOP/s", "nominal_peak": PEAK_TFLOPS["bf16"],
                           **{kind: mfma_ceiling(attn, torch, zero) for kind, zero in (("random", False), ("zeros", True))}}))
@@ -231,6 +231,7 @@ def main():
                      "traffic": traffic, "traffic_source": "profiles/hbm_traffic.json (rocprofv3 --pmc, recorded)",
                      "traffic_stale": traffic_stale, "kernels": kernels},
         "io_bound": bound,
+        "source_hash": pmc_summary.source_hash(),  # of csrc/ and include/: what this line was measured on
         "traffic_over_yardstick": (traffic / bound["yardstick_bytes"]) if traffic else None,
     }
     if w.dtype == "bf16":

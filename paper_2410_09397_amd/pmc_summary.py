@@ -52,7 +52,7 @@ def _one(pattern):
 
 
 def short(name):
-    return name.split("(")[0].replace("void ", "").replace("attn::", "")
+    return name.replace("(anonymous namespace)::", "").split("(")[0].replace("void ", "").replace("attn::", "")
 
 
 def kernel_stats(d):
@@ -132,10 +132,12 @@ def main():
     lines.append("python -m paper_2410_09397_amd.pmc_summary --workload %s --workload-index %d%s --stats %s --fetch %s "
                  "--write %s" % (args.workload, w, shape, args.stats, args.fetch, args.write))
     lines.append("```\n")
+    measured_hash = source_hash()  # replaced by the hash the profiled run itself reports, when it does
     if args.bench_json and os.path.exists(args.bench_json):
         for l in open(args.bench_json):
             if l.startswith("{"):
                 j = json.loads(l)
+                measured_hash = j.get("source_hash", measured_hash)
                 lines.append("bench.py line of the kernel-trace run: value %.1f %s, bwd %.3f ms, fwd %.3f ms, "
                              "ms_per_step %.3f\n" % (j["value"], j["unit"], j["bwd_ms"], j["fwd_ms"], j["ms_per_step"]))
     lines.append("Calibration (plain 1 GiB device copy in the same run): FETCH_SIZE reads %.1f -> factor %.3f; "
@@ -183,17 +185,129 @@ def main():
                  bwd_bytes / y, y / 1e6))
         return
     key = traffic_key(args.workload, args.tiling)
-    lines.append("Kernel sources: hash %s (paper_2410_09397_amd.pmc_summary.source_hash)." % source_hash())
+    lines.append("Kernel sources: hash %s (paper_2410_09397_amd.pmc_summary.source_hash)." % measured_hash)
     with open(os.path.join(out_dir, "attn_kernels_%s.md" % key.replace("@", "_")), "w") as fh:
         fh.write("\n".join(lines) + "\n")
     tpath = os.path.join(out_dir, "hbm_traffic.json")
     traffic = json.load(open(tpath)) if os.path.exists(tpath) else {}
     traffic[key] = {"bytes": bwd_bytes, "read": tot["bwd"][1], "written": tot["bwd"][2], "bwd_ms_summed": tot["bwd"][0] / 1e6,
-                    "source_hash": source_hash()}
+                    "source_hash": measured_hash}
     with open(tpath, "w") as fh:
         json.dump(traffic, fh, indent=1, sort_keys=True)
     print("\n".join(lines))
 
 
+
+
+# ------------------------------------------------------------------ compiler resource usage
+def resources_main():
+    """python -m paper_2410_09397_amd.pmc_summary resources  -> markdown table of registers, scratch and
+    occupancy of every kernel, from hipcc -Rpass-analysis=kernel-resource-usage on the committed sources."""
+    import re
+    import subprocess
+    from paper_2410_09397_amd import build as hip_build
+    rows = []
+    for src in hip_build.SOURCES:
+        cmd = ["hipcc", *hip_build.FLAGS, "-Rpass-analysis=kernel-resource-usage", "-c",
+               os.path.join(hip_build.CSRC, src), "-o", os.devnull]
+        err = subprocess.run(cmd, capture_output=True, text=True).stderr
+        cur = None
+        for line in err.splitlines():
+            m = re.search(r"remark: (?:Function Name: (\S+)|\s+(\S[^:]*): (\S+))", line)
+            if not m:
+                continue
+            if m.group(1):
+                name = subprocess.run(["c++filt", m.group(1)], capture_output=True, text=True).stdout.strip()
+                if name.startswith("_Z"):  # c++filt does not know the bf16 type code
+                    name = re.sub(r"^_ZN4attn\d+(\w+?)IDF16bEEv.*$", r"\1<bf16>", name)
+                cur = {"kernel": short(name)}
+                rows.append(cur)
+            elif cur is not None:
+                cur[m.group(2).strip()] = m.group(3)
+    print("## Compiler resource usage (`hipcc -Rpass-analysis=kernel-resource-usage`, gfx950)\n")
+    print("| kernel | VGPRs | AGPRs | scratch (bytes/lane) | occupancy (waves/SIMD) |")
+    print("|---|---|---|---|---|")
+    for r in rows:
+        print("| %s | %s | %s | %s | %s |" % (r["kernel"], r.get("VGPRs", "?"), r.get("AGPRs", "?"),
+                                         r.get("ScratchSize [bytes/lane]", "?"), r.get("Occupancy [waves/SIMD]", "?")))
+
+
+# ------------------------------------------------------------------------------ SQ counters
+SQ_PASSES = (
+    "SQ_WAVE_CYCLES SQ_BUSY_CYCLES SQ_WAIT_ANY SQ_WAIT_INST_ANY SQ_WAIT_INST_LDS SQ_ACTIVE_INST_VALU "
+    "SQ_VALU_MFMA_BUSY_CYCLES SQ_ACTIVE_INST_LDS",
+    "SQ_INSTS_VALU SQ_INSTS_MFMA SQ_INSTS_LDS SQ_INSTS_SALU SQ_INSTS_VALU_TRANS_F32 SQ_INST_LEVEL_LDS SQ_INSTS_VMEM "
+    "SQ_LDS_BANK_CONFLICT",
+    "SQ_LDS_IDX_ACTIVE SQ_LDS_ADDR_CONFLICT SQ_LDS_DATA_FIFO_FULL SQ_LDS_CMD_FIFO_FULL SQ_BUSY_CU_CYCLES "
+    "SQ_ACTIVE_INST_ANY SQ_VALU_MFMA_COEXEC_CYCLES SQ_ACTIVE_INST_MISC",
+)
+
+
+def sq_main(argv):
+    """python -m paper_2410_09397_amd.pmc_summary sq --workload NAME --bench-args "..." DIR1 DIR2 DIR3
+    -> profiles/sq_counters_<NAME>.md from the three rocprofv3 --pmc passes listed in SQ_PASSES."""
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--workload", required=True)
+    ap.add_argument("--bench-args", default="")
+    ap.add_argument("--resources", default=None, help="file with the compiler's kernel-resource-usage table to append")
+    ap.add_argument("dirs", nargs=3)
+    args = ap.parse_args(argv)
+    vals = collections.defaultdict(dict)
+    for d in args.dirs:
+        acc = collections.defaultdict(list)
+        with open(_one(os.path.join(d, "**", "*counter_collection.csv"))) as fh:
+            for r in csv.DictReader(fh):
+                acc[(short(r["Kernel_Name"]), r["Counter_Name"])].append(float(r["Counter_Value"]))
+        for (k, c), v in acc.items():
+            vals[k][c] = sum(v) / len(v)
+    kernels = [k for k in vals if is_in(k, BWD_KERNELS + FWD_KERNELS + ("mfma_ceiling_kernel",)) and vals[k].get("SQ_INSTS_MFMA", 0) > 0]
+    lines = ["# SQ counters of the attention kernels, workload %s\n" % args.workload,
+             "Three `rocprofv3 --pmc` passes of the same command (8 SQ counters each; from the repository root on one MI355X,",
+             "after `cd /tmp && export TMPDIR=/tmp`), then this summary:\n", "```"]
+    for i, p in enumerate(SQ_PASSES):
+        lines.append("rocprofv3 --pmc %s -d %s -o pmc --output-format csv -- python bench.py %s --steps 3 --warmup 1 --sustain 0 "
+                     "--no-kernel-split --no-cpu-baseline" % (p, args.dirs[i], args.bench_args))
+    lines.append("python -m paper_2410_09397_amd.pmc_summary sq --workload %s --bench-args \"%s\" %s" %
+                 (args.workload, args.bench_args, " ".join(args.dirs)))
+    lines.append("```\n")
+    lines.append("Values are averages per dispatch, summed over the device.  `mfma_ceiling_kernel` is the library's register-only MFMA loop")
+    lines.append("(two waves per SIMD, nothing but MFMAs), which `bench.py` runs at the end: its row shows what the counters read for a matrix")
+    lines.append("pipe that is never idle.\n")
+    counters = [c for p in SQ_PASSES for c in p.split()]
+    lines.append("| counter | " + " | ".join(kernels) + " |")
+    lines.append("|---|" + "---|" * len(kernels))
+    for c in counters:
+        lines.append("| %s | " % c + " | ".join("%.4g" % vals[k].get(c, float("nan")) for k in kernels) + " |")
+    lines.append("\nDerived:\n")
+    lines.append("| ratio | " + " | ".join(kernels) + " |")
+    lines.append("|---|" + "---|" * len(kernels))
+
+    def ratio(a, b, scale=1.0):
+        return " | ".join("%.3f" % (scale * vals[k].get(a, float("nan")) / vals[k][b]) if vals[k].get(b) else "-" for k in kernels)
+    lines.append("| MFMA busy cycles / (4 SIMDs x CU busy cycles) | %s |" % ratio("SQ_VALU_MFMA_BUSY_CYCLES", "SQ_BUSY_CU_CYCLES", 0.25))
+    lines.append("| VALU instructions (incl. MFMA) per MFMA | %s |" % ratio("SQ_INSTS_VALU", "SQ_INSTS_MFMA"))
+    lines.append("| transcendental instructions per MFMA | %s |" % ratio("SQ_INSTS_VALU_TRANS_F32", "SQ_INSTS_MFMA"))
+    lines.append("| LDS instructions per MFMA | %s |" % ratio("SQ_INSTS_LDS", "SQ_INSTS_MFMA"))
+    lines.append("| SALU instructions per MFMA | %s |" % ratio("SQ_INSTS_SALU", "SQ_INSTS_MFMA"))
+    lines.append("| LDS bank-conflict cycles / LDS active cycles | %s |" % ratio("SQ_LDS_BANK_CONFLICT", "SQ_LDS_IDX_ACTIVE"))
+    lines.append("| LDS data-FIFO-full cycles / CU busy cycles | %s |" % ratio("SQ_LDS_DATA_FIFO_FULL", "SQ_BUSY_CU_CYCLES"))
+    lines.append("| wave cycles waiting on LDS instructions / wave cycles | %s |" % ratio("SQ_WAIT_INST_LDS", "SQ_WAVE_CYCLES"))
+    lines.append("| wave cycles waiting on any instruction / wave cycles | %s |" % ratio("SQ_WAIT_INST_ANY", "SQ_WAVE_CYCLES"))
+    lines.append("| MFMA and VALU co-executing cycles / MFMA busy cycles | %s |" % ratio("SQ_VALU_MFMA_COEXEC_CYCLES", "SQ_VALU_MFMA_BUSY_CYCLES"))
+    if args.resources and os.path.exists(args.resources):
+        lines.append("\n" + open(args.resources).read().rstrip())
+    lines.append("\nKernel sources: hash %s." % source_hash())
+    out = os.path.join(ROOT, "profiles", "sq_counters_%s.md" % args.workload)
+    with open(out, "w") as fh:
+        fh.write("\n".join(lines) + "\n")
+    print("\n".join(lines))
+
+
 if __name__ == "__main__":
-    main()
+    import sys
+    if len(sys.argv) > 1 and sys.argv[1] == "sq":
+        sq_main(sys.argv[2:])
+    elif len(sys.argv) > 1 and sys.argv[1] == "resources":
+        resources_main()
+    else:
+        main()
