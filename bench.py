@@ -62,6 +62,43 @@ def load_traffic(name, tiling):
     return float(entry["bytes"]), entry.get("source_hash") != pmc_summary.source_hash()
 
 
+def quick_workload(index, steps=10, warmup=3):
+    """One of the metric's other configurations, timed briefly with the library's own choices: median backward
+    and forward time over `steps` steps (HIP events around each call)."""
+    import torch
+    from paper_2410_09397_amd import attn, io_bound, synth
+    w = synth.workload(index)
+    dt = {"bf16": torch.bfloat16, "f32": torch.float32}[w.dtype]
+    inp = synth.make_inputs(w)
+    Q, K, V, dO = (torch.from_numpy(inp[t]).to("cuda").to(dt) for t in ("Q", "K", "V", "dO"))
+    mask = attn.BlockMask(inp["keep"], w.block, w.n) if w.sparse else None
+    O, LSE = torch.empty_like(Q), torch.empty(Q.shape[:3], dtype=torch.float32, device="cuda")
+    grads = tuple(torch.empty_like(Q) for _ in range(3))
+    ws = torch.empty(max(attn.attn_workspace_bytes(attn._desc(Q, w.scale, w.causal), mask), 256), dtype=torch.uint8, device="cuda")
+    fwd_t, bwd_t = [], []
+    for k in range(warmup + steps):
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        e[0].record()
+        attn.attn_fwd(Q, K, V, w.scale, causal=w.causal, mask=mask, out=(O, LSE), workspace=ws)
+        e[1].record()
+        if mask is not None:
+            attn.attn_bwd_blocksparse(Q, K, V, O, dO, LSE, w.scale, mask, causal=w.causal, out=grads, workspace=ws)
+        else:
+            attn.attn_bwd(Q, K, V, O, dO, LSE, w.scale, causal=w.causal, out=grads, workspace=ws)
+        e[2].record()
+        torch.cuda.synchronize()
+        if k >= warmup:
+            fwd_t.append(e[0].elapsed_time(e[1]))
+            bwd_t.append(e[1].elapsed_time(e[2]))
+    fwd_ms, bwd_ms = sorted(fwd_t)[steps // 2], sorted(bwd_t)[steps // 2]
+    traffic, stale = load_traffic(w.name, 0)
+    tf = w.bwd_flops() / (bwd_ms * 1e-3) * 1e-12
+    return {"workload": w.name, "dtype": w.dtype, "steps": steps, "bwd_ms": bwd_ms, "fwd_ms": fwd_ms, "bwd_tflops": tf,
+            "frac": tf / PEAK_TFLOPS[w.dtype], "fwd_tflops": w.fwd_flops() / (fwd_ms * 1e-3) * 1e-12,
+            "traffic": traffic, "traffic_stale": stale,
+            "traffic_over_yardstick": (traffic / io_bound.report(w)["yardstick_bytes"]) if traffic else None}
+
+
 def mfma_ceiling(attn, torch, zero_operands, iters=150000):
     """Rate and clock of the library's register-only MFMA loop: a short warm-up launch, then `iters`
     iterations (about 40 ms at the clock random operands allow)."""
@@ -94,6 +131,10 @@ def main():
     ap.add_argument("--no-kernel-split", action="store_true",
                     help="do not time the two kernels of the two-kernel tiling one at a time (profiling runs: "
                          "every launch of the run then belongs to a whole step)")
+    ap.add_argument("--other-workloads", dest="other_workloads", action="store_true", default=None,
+                    help="also time the metric's other configurations briefly (10 steps each) and report them in "
+                         "\"other_workloads\" (default: only beside the plain default run)")
+    ap.add_argument("--no-other-workloads", dest="other_workloads", action="store_false")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--wgrad", action="store_true",
                     help="also time attn_bwd_wgrad (the paper's weight gradient) on the same shape and "
@@ -259,6 +300,11 @@ def main():
         flops = bh * (6.0 * w.n * w.n * w.d * w.kept_fraction() + 6.0 * w.n * w.d * w.d)
         out["wgrad"] = {"ms": ms, "algorithmic_tflops": flops / (ms * 1e-3) * 1e-12,
                         "note": "projections + forward + dQ kernel + A_1^T dQ; executes 10 n^2 d per pair"}
+    if args.other_workloads is None:  # by default only beside the plain default run
+        args.other_workloads = (args.workload == 3 and not args.shape and args.extra_frac is None and not args.tiling
+                                and not args.zero_operands and not args.calibrate_copy and not args.no_kernel_split)
+    if args.other_workloads:
+        out["other_workloads"] = [quick_workload(i) for i in (1, 2, 4, 5) if i != args.workload]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))
