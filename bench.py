@@ -156,7 +156,9 @@ def main():
     from paper_2410_09397_amd import attn, io_bound, pmc_summary, synth
     if args.mfma_ceiling:
         print(json.dumps({"probe": "mfma_ceiling", "unit": "TFLOP/s", "nominal_peak": PEAK_TFLOPS["bf16"],
-                          **{kind: mfma_ceiling(attn, torch, zero) for kind, zero in (("random", False), ("zeros", True))}}))
+                          **{kind: mfma_ceiling(attn, torch, mode) for kind, mode in
+                             (("random", 0), ("zeros", 1), ("random_b_operand_from_lds", 2),
+                              ("random_b_from_lds_plus_vector_arithmetic", 3))}}))
         return
     w = synth.workload(args.workload)
     if args.shape:
@@ -278,7 +280,7 @@ def main():
     if w.dtype == "bf16":
         # context for `frac`: what a register-only MFMA loop sustains on this GPU for random operands
         # (the clock under matrix load follows the power the data draws; `peak` assumes 2.4 GHz)
-        out["mfma_ceiling_random_operands"] = mfma_ceiling(attn, torch, False)
+        out["mfma_ceiling_random_operands"] = mfma_ceiling(attn, torch, 0)
     if args.wgrad and w.dtype == "bf16" and w.d in (64, 128, 256) and not w.sparse:
         del grads, O, ws
         wi = synth.make_wgrad_inputs(w)

@@ -192,7 +192,10 @@ attn_status attn_blockmask_validate(int32_t block, int32_t nblk, int32_t n, int3
 /*
  * Measurement aid (no part of the attention path; the paper has no counterpart): launches a
  * register-only loop of independent dense bf16 MFMAs (32x32x16) on every CU, two waves per SIMD,
- * `iters` iterations of 8 MFMAs per wave, on random (zero_operands = 0) or all-zero operands.
+ * `iters` iterations of 8 MFMAs per wave.  `operands`: 0 = random bf16 operands held in registers,
+ * 1 = all-zero operands, 2 = random operands with the B operand of every MFMA read from LDS as a fresh
+ * 1 KB fragment (what the attention kernels do), 3 = as 2 plus four fp32 multiply-adds and one
+ * exponential per MFMA (about the vector arithmetic of the backward kernels).
  * The rate it sustains is the ceiling of any kernel built on that instruction for operands of
  * that kind: under matrix load the shader clock follows the power the data's switching activity
  * draws.  Asynchronous on `stream`; the caller times it.
@@ -201,9 +204,9 @@ attn_status attn_blockmask_validate(int32_t block, int32_t nblk, int32_t n, int3
  *              has been synchronised
  *   flops      HOST double[1]: floating-point operations the launch executes
  * Errors: ATTN_ERR_INVALID_ARG (iters outside 1 .. 4 000 000, i.e. about a second of GPU time;
- * null pointers), ATTN_ERR_DEVICE.
+ * operands outside 0 .. 3; null pointers), ATTN_ERR_DEVICE.
  */
-attn_status attn_mfma_ceiling(int32_t iters, int32_t zero_operands, float *clock_ghz, double *flops,
+attn_status attn_mfma_ceiling(int32_t iters, int32_t operands, float *clock_ghz, double *flops,
                               void *stream);
 
 /* Static description of a status code. */

@@ -266,14 +266,14 @@ def attn_bwd_wgrad(A1, A2, A3, X, Y, dO, scale=1.0, causal=False, stream=None, o
     return g
 
 
-def attn_mfma_ceiling(iters, zero_operands=False, stream=None):
+def attn_mfma_ceiling(iters, operands=0, stream=None):
     """Launches the register-only MFMA loop (include/attn_mi355x.h).  Returns (clock, flops): a
     device float tensor that holds the shader clock in GHz once the stream is synchronised, and
     the number of floating-point operations of the launch."""
     import torch
     clock = torch.zeros(1, dtype=torch.float32, device="cuda")
     flops = ctypes.c_double(0.0)
-    st = lib().attn_mfma_ceiling(int(iters), int(bool(zero_operands)), clock.data_ptr(), ctypes.byref(flops),
+    st = lib().attn_mfma_ceiling(int(iters), int(operands), clock.data_ptr(), ctypes.byref(flops),
                                  _stream(stream))
     if st != ATTN_OK:
         raise AttnError(st, "attn_mfma_ceiling")

@@ -33,6 +33,11 @@ __device__ __forceinline__ unsigned random_bf16x2(unsigned seed) {
     return lo | (hi << 16);
 }
 
+// MODE 0: operands stay in registers.  MODE 1: the B operand of every MFMA is a fresh 1 KB fragment read from LDS
+// (ds_read_b128 per lane, conflict-free), which is what the attention kernels do.  MODE 2: in addition one exponential
+// and four other fp32 instructions per MFMA, independent of one another: about the vector arithmetic of the
+// backward kernels per MFMA.
+template <int MODE>
 __global__ void __launch_bounds__(kThreads) mfma_ceiling_kernel(float* result, int iters, int zero_operands) {
     extern __shared__ char smem[];
     const int tid = threadIdx.x;
@@ -42,16 +47,42 @@ __global__ void __launch_bounds__(kThreads) mfma_ceiling_kernel(float* result, i
         au[i] = zero_operands ? 0u : random_bf16x2(tid * 31u + i + blockIdx.x * 7919u);
         bu[i] = zero_operands ? 0u : random_bf16x2(tid * 57u + i + 99u);
     }
-    const bf16x8 a = __builtin_bit_cast(bf16x8, au), b = __builtin_bit_cast(bf16x8, bu);
+    const bf16x8 a = __builtin_bit_cast(bf16x8, au);
+    bf16x8 b = __builtin_bit_cast(bf16x8, bu);
+    if (MODE >= 1) {  // 8 fragments of 1 KB per wave in LDS, random (or zero) like the register operands
+#pragma unroll
+        for (int j = 0; j < kProbeMfmaPerIter; ++j) {
+            u32x4 v;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] = zero_operands ? 0u : random_bf16x2(tid * 131u + j * 17u + i);
+            *reinterpret_cast<u32x4*>(smem + (j * kThreads + tid) * 16) = v;
+        }
+        __syncthreads();
+    }
     f32x16 acc[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[j][i] = 0.f;
+    float v[kProbeMfmaPerIter];
+#pragma unroll
+    for (int j = 0; j < kProbeMfmaPerIter; ++j) v[j] = 0.37f + tid * 1e-3f + j;
     const long c0 = clock64(), w0 = wall_clock64();
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int j = 0; j < kProbeMfmaPerIter; ++j) acc[j & 3] = mfma32(a, b, acc[j & 3]);
+        for (int j = 0; j < kProbeMfmaPerIter; ++j) {
+            if (MODE >= 1) {
+                b = *reinterpret_cast<const bf16x8*>(smem + (j * kThreads + tid) * 16);
+                asm volatile("" : "+v"(b));  // a read per MFMA: not hoisted out of the loop
+            }
+            acc[j & 3] = mfma32(a, b, acc[j & 3]);
+            if (MODE >= 2) {  // independent of one another and of the MFMAs: v[j] is touched once per iteration
+                const float e = __builtin_amdgcn_exp2f(v[j] * 0.5f - 1.f);
+                v[j] = (e - 0.25f) * v[j] + 0.3f;
+                v[(j + 4) & 7] = v[(j + 4) & 7] * 0.999f + 0.001f;
+                asm volatile("" : "+v"(v[j]));
+            }
+        }
         if ((it & 1023) == 1023) {  // the sums are random walks: pull them back now and then
 #pragma unroll
             for (int j = 0; j < 4; ++j)
@@ -63,6 +94,8 @@ __global__ void __launch_bounds__(kThreads) mfma_ceiling_kernel(float* result, i
     if (tid == 0 && blockIdx.x == gridDim.x / 2)
         result[0] = (float)((double)(clock64() - c0) / (double)(wall_clock64() - w0)) * 0.1f;
     float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < kProbeMfmaPerIter; ++j) s += v[j];
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -77,17 +110,24 @@ __global__ void __launch_bounds__(kThreads) mfma_ceiling_kernel(float* result, i
 #pragma GCC visibility push(default)
 extern "C" {
 
-attn_status attn_mfma_ceiling(int32_t iters, int32_t zero_operands, float* clock_ghz, double* flops, void* stream) {
+attn_status attn_mfma_ceiling(int32_t iters, int32_t operands, float* clock_ghz, double* flops, void* stream) {
     if (iters < 1 || iters > 4000000 || !clock_ghz || !flops) return ATTN_ERR_INVALID_ARG;  // <= about 1 s of GPU time
+    if (operands < 0 || operands > 3) return ATTN_ERR_INVALID_ARG;
+    const int zero_operands = operands == 1, mode = operands >= 2 ? operands - 1 : 0;
+    const void* fn = mode == 0   ? reinterpret_cast<const void*>(attn::mfma_ceiling_kernel<0>)
+                     : mode == 1 ? reinterpret_cast<const void*>(attn::mfma_ceiling_kernel<1>)
+                                 : reinterpret_cast<const void*>(attn::mfma_ceiling_kernel<2>);
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess) return ATTN_ERR_DEVICE;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return ATTN_ERR_DEVICE;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(attn::mfma_ceiling_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, attn::kProbeLds) != hipSuccess)
+    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, attn::kProbeLds) != hipSuccess)
         return ATTN_ERR_DEVICE;
     const int blocks = attn::kProbeBlocksPerCu * cus;
-    hipLaunchKernelGGL(attn::mfma_ceiling_kernel, dim3((unsigned)blocks), dim3(attn::kThreads), attn::kProbeLds,
-                       static_cast<hipStream_t>(stream), clock_ghz, iters, zero_operands);
+    const dim3 grid((unsigned)blocks), block(attn::kThreads);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (mode == 0) hipLaunchKernelGGL(attn::mfma_ceiling_kernel<0>, grid, block, attn::kProbeLds, s, clock_ghz, iters, zero_operands);
+    else if (mode == 1) hipLaunchKernelGGL(attn::mfma_ceiling_kernel<1>, grid, block, attn::kProbeLds, s, clock_ghz, iters, zero_operands);
+    else hipLaunchKernelGGL(attn::mfma_ceiling_kernel<2>, grid, block, attn::kProbeLds, s, clock_ghz, iters, zero_operands);
     if (hipGetLastError() != hipSuccess) return ATTN_ERR_DEVICE;
     // 32 x 32 x 16 multiply-adds per MFMA and wave
     *flops = (double)blocks * (attn::kThreads / 64) * attn::kProbeMfmaPerIter * (double)iters * 2.0 * 32 * 32 * 16;
