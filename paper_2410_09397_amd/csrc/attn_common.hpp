@@ -299,11 +299,17 @@ __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(
 template <int TILE>
 __device__ __forceinline__ int tile_start_row(const int32_t* list_idx, int lp0, int t0, int it) {
     constexpr int kSub = 128 / TILE;
+    // the result is uniform and is made a scalar here: every address derived from it (tile copies, row
+    // statistics) is then scalar arithmetic, not vector instructions that would compete with the MFMAs
     if (list_idx) {
         const int e = __builtin_amdgcn_readfirstlane(lp0 + it / kSub);
-        return list_idx[e] * 128 + (it % kSub) * TILE;
+        // read through the constant address space: a scalar load (the lists are never written by these kernels),
+        // which neither occupies a vector register nor waits behind the tile copies and atomics in flight
+        typedef const int32_t __attribute__((address_space(4))) * const_i32_ptr;
+        const const_i32_ptr cidx = (const_i32_ptr)(unsigned long long)list_idx;
+        return cidx[e] * 128 + (it % kSub) * TILE;
     }
-    return (t0 + it) * TILE;
+    return __builtin_amdgcn_readfirstlane((t0 + it) * TILE);
 }
 
 // Block lists under the causal rule.  The row list of query block b (ascending key blocks) only
