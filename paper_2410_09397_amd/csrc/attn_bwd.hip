@@ -482,6 +482,14 @@ __global__ void __launch_bounds__(kThreads, D == 64 ? 4 : (QT == 1 && D <= 128 ?
         settle(lse2[t]);
         settle(dl[t]);
     }
+    // -delta of this lane's query in all 16 registers of an accumulator block: the dP^T chains start
+    // from it (C operand of their first MFMA), so dP^T - delta costs no vector instruction per tile
+    f32x16 ndl[QT];
+#pragma unroll
+    for (int t = 0; t < QT; ++t) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) ndl[t][i] = -dl[t];
+    }
     FragOffsets<D> lane_offsets;
     lane_offsets.init(lane);
     FragAddrs<D> fo;
@@ -505,7 +513,9 @@ __global__ void __launch_bounds__(kThreads, D == 64 ? 4 : (QT == 1 && D <= 128 ?
 #pragma unroll
             for (int t = 0; t < QT; ++t)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) { st[t][i] = 0.f; dpt[t][i] = 0.f; }
+                for (int i = 0; i < 16; ++i) st[t][i] = 0.f;
+#pragma unroll
+            for (int t = 0; t < QT; ++t) dpt[t] = ndl[t];
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {  // independent accumulation chains, interleaved
                 const bf16x8 kfr = fo.frag(smem, k_off, 32 * T, ks);
@@ -527,7 +537,7 @@ __global__ void __launch_bounds__(kThreads, D == 64 ? 4 : (QT == 1 && D <= 128 ?
                 for (int i = 0; i < 16; ++i) {
                     float pv = __builtin_amdgcn_exp2f(st[t][i] * c - lse2[t]);
                     if constexpr (decltype(masked)::value) pv = (8 * (i >> 2) + (i & 3) > lim) ? 0.f : pv;
-                    dpt[t][i] = pv * (dpt[t][i] - dl[t]);
+                    dpt[t][i] = pv * dpt[t][i];
                 }
 #pragma unroll
                 for (int ss = 0; ss < 2; ++ss) dsb[t][ss] = acc_to_operand(dpt[t], ss);
