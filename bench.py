@@ -158,7 +158,7 @@ def main():
         print(json.dumps({"probe": "mfma_ceiling", "unit": "TFLOP/s", "nominal_peak": PEAK_TFLOPS["bf16"],
                           **{kind: mfma_ceiling(attn, torch, mode) for kind, mode in
                              (("random", 0), ("zeros", 1), ("random_b_operand_from_lds", 2),
-                              ("random_b_from_lds_plus_vector_arithmetic", 3))}}))
+                              ("random_b_from_lds_plus_vector_arithmetic", 3), ("dkdv_tile_loop_without_dependencies", 4))}}))
         return
     w = synth.workload(args.workload)
     if args.shape:

@@ -194,8 +194,12 @@ attn_status attn_blockmask_validate(int32_t block, int32_t nblk, int32_t n, int3
  * register-only loop of independent dense bf16 MFMAs (32x32x16) on every CU, two waves per SIMD,
  * `iters` iterations of 8 MFMAs per wave.  `operands`: 0 = random bf16 operands held in registers,
  * 1 = all-zero operands, 2 = random operands with the B operand of every MFMA read from LDS as a fresh
- * 1 KB fragment (what the attention kernels do), 3 = as 2 plus four fp32 multiply-adds and one
- * exponential per MFMA (about the vector arithmetic of the backward kernels).
+ * 1 KB fragment requested one MFMA ahead (what the attention kernels do), 3 = as 2 plus four fp32
+ * multiply-adds and one exponential per MFMA (about the vector arithmetic of the backward kernels),
+ * 4 = the instruction stream of one wave of the dK / dV kernel per 64 x 64 tile at d = 128 with every
+ * dependency taken out (per 32 MFMAs: 16 ds_read_b128 and 32 ds_read_b64_tr_b16 fragment reads, 16
+ * exponentials, 64 multiply-adds, 16 bf16 packs, 8 LDS writes, 8 KB of global_load_lds tile copy out of
+ * a 1 MB window, two workgroup barriers); `iters` still counts 8 MFMAs, a tile is four of them.
  * The rate it sustains is the ceiling of any kernel built on that instruction for operands of
  * that kind: under matrix load the shader clock follows the power the data's switching activity
  * draws.  Asynchronous on `stream`; the caller times it.
@@ -204,7 +208,7 @@ attn_status attn_blockmask_validate(int32_t block, int32_t nblk, int32_t n, int3
  *              has been synchronised
  *   flops      HOST double[1]: floating-point operations the launch executes
  * Errors: ATTN_ERR_INVALID_ARG (iters outside 1 .. 4 000 000, i.e. about a second of GPU time;
- * operands outside 0 .. 3; null pointers), ATTN_ERR_DEVICE.
+ * operands outside 0 .. 4; null pointers), ATTN_ERR_DEVICE.
  */
 attn_status attn_mfma_ceiling(int32_t iters, int32_t operands, float *clock_ghz, double *flops,
                               void *stream);

@@ -14,9 +14,9 @@ def test_mfma_ceiling_runs_and_reports():
     assert 0.5 < float(clock.item()) < 3.0   # GHz
     with pytest.raises(attn.AttnError):
         attn.attn_mfma_ceiling(0)
-    for operands in (1, 2, 3):  # zero operands; B operand from LDS; plus vector arithmetic
+    for operands in (1, 2, 3, 4):  # zero operands; B operand from LDS; plus vector arithmetic; tile-loop skeleton
         clock, f2 = attn.attn_mfma_ceiling(500, operands)
         torch.cuda.synchronize()
         assert f2 == flops / 4 and 0.5 < float(clock.item()) < 3.0
     with pytest.raises(attn.AttnError):
-        attn.attn_mfma_ceiling(10, 4)
+        attn.attn_mfma_ceiling(10, 5)
