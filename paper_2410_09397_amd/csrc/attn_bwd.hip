@@ -76,6 +76,40 @@ __global__ void __launch_bounds__(kThreads) block_order_kernel(const int32_t* le
     order[rank] = i;
 }
 
+// Both steps, for the row lists and the column lists of a mask, in one launch when a mask has at most
+// kOrderFusedBlocks blocks: workgroup (mask, kind) keeps the lengths in LDS and ranks them there (four small
+// launches in front of the backward kernels cost as much as 2 % of a block-sparse call).
+constexpr int kOrderFusedBlocks = 256;
+__global__ void __launch_bounds__(kThreads) block_order_fused_kernel(const int32_t* row_ptr, const int32_t* col_idx,
+                                                                    const int32_t* col_ptr, const int32_t* row_idx,
+                                                                    int nblk, int causal, int32_t* order_q,
+                                                                    int32_t* order_k, int first_kind) {
+    __shared__ int32_t len[kOrderFusedBlocks];
+    const int kind = first_kind + blockIdx.y;  // 0: row lists (query blocks), 1: column lists (key blocks)
+    const int32_t* ptr = (kind ? col_ptr : row_ptr) + (long)blockIdx.x * (nblk + 1);  // mask blockIdx.x
+    const int32_t* idx = kind ? row_idx : col_idx;
+    int32_t* order = (kind ? order_k : order_q) + (long)blockIdx.x * nblk;
+    for (int i = threadIdx.x; i < nblk; i += kThreads) {
+        const int first = ptr[i];
+        int count = ptr[i + 1] - first;
+        if (causal) {
+            if (kind) count -= causal_col_skip(idx, first, count, i);
+            else count = causal_row_entries(idx, first, count, i);
+        }
+        len[i] = count;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < nblk; i += kThreads) {
+        const int mine = len[i];
+        int rank = 0;
+        for (int k = 0; k < nblk; ++k) {
+            const int other = len[k];
+            rank += (other > mine || (other == mine && k < i)) ? 1 : 0;
+        }
+        order[rank] = i;
+    }
+}
+
 // ------------------------------------------------------------------------------- dK, dV
 // A workgroup owns 64 keys and streams 64-query tiles; per tile its 4 waves work in two phases:
 //   phase 1: wave (wk, wx) computes S^T and dP^T for key half wk and query half wx, with the
@@ -645,13 +679,21 @@ static hipError_t launch_bwd(const FusedParams& p, const int32_t* csr_ptr, const
         order_k = order_scratch + (long)masks * blocks128;
         int32_t* len = order_scratch + 2L * masks * blocks128;
         const dim3 og((unsigned)((blocks128 + kThreads - 1) / kThreads), (unsigned)masks);
-        if (!onepass && !dkdv_only) {
-            hipLaunchKernelGGL(block_len_kernel, og, dim3(kThreads), 0, stream, csr_ptr, csr_idx, blocks128, p.causal, 0, len);
-            hipLaunchKernelGGL(block_order_kernel, og, dim3(kThreads), 0, stream, len, blocks128, order_q);
-        }
-        if (!dq_only) {
-            hipLaunchKernelGGL(block_len_kernel, og, dim3(kThreads), 0, stream, csc_ptr, csc_idx, blocks128, p.causal, 1, len);
-            hipLaunchKernelGGL(block_order_kernel, og, dim3(kThreads), 0, stream, len, blocks128, order_k);
+        const bool want_q = !onepass && !dkdv_only, want_k = !dq_only;
+        if (blocks128 <= kOrderFusedBlocks) {
+            if (want_q || want_k)
+                hipLaunchKernelGGL(block_order_fused_kernel, dim3((unsigned)masks, want_q && want_k ? 2u : 1u),
+                                   dim3(kThreads), 0, stream, csr_ptr, csr_idx, csc_ptr, csc_idx, blocks128, p.causal,
+                                   order_q, order_k, want_q ? 0 : 1);
+        } else {
+            if (want_q) {
+                hipLaunchKernelGGL(block_len_kernel, og, dim3(kThreads), 0, stream, csr_ptr, csr_idx, blocks128, p.causal, 0, len);
+                hipLaunchKernelGGL(block_order_kernel, og, dim3(kThreads), 0, stream, len, blocks128, order_q);
+            }
+            if (want_k) {
+                hipLaunchKernelGGL(block_len_kernel, og, dim3(kThreads), 0, stream, csc_ptr, csc_idx, blocks128, p.causal, 1, len);
+                hipLaunchKernelGGL(block_order_kernel, og, dim3(kThreads), 0, stream, len, blocks128, order_k);
+            }
         }
     }
     if (onepass) {

@@ -21,7 +21,7 @@ import os
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 COPY_BYTES = float(1 << 30)  # bytes read, and bytes written, by the calibration copy
 BWD_KERNELS = ("delta_kernel", "bwd_dkdv", "bwd_dq", "ld_scores_kernel<2,", "ld_gemm_kernel", "generic_delta",
-               "generic_dq", "generic_dkdv", "block_len_kernel", "block_order_kernel", "bwd_prep_kernel",
+               "generic_dq", "generic_dkdv", "block_len_kernel", "block_order_kernel", "block_order_fused_kernel", "bwd_prep_kernel",
                "bwd_onepass_kernel", "bwd_splitd_kernel")
 
 

@@ -40,6 +40,8 @@ MORE = [
                    per_head_masks=True),
     # the longest sequence the tests run: 512 streamed tiles per workgroup
     synth.Workload("full_d128_n32768_causal", 75, 1, 1, 32768, 128, "bf16", causal=True),
+    # more than 256 blocks per mask: the block-order lists come from the two-step kernels, not the fused one
+    synth.Workload("full_d64_n33000_sparse", 76, 1, 1, 33000, 64, "bf16", sparse=True, extra_frac=0.02),
 ]
 
 
