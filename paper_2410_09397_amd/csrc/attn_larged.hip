@@ -42,6 +42,8 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) ld_scores_kernel(Lar
     constexpr int BK = 32, kKeys = 32 * NW, kThreadsHere = 64 * NW;
     constexpr int kTileK = kKeys * BK * 2, kTileQ = 128 * BK * 2;  // bytes per operand tile
     constexpr int kStage = (MODE == kBackward ? 2 : 1) * (kTileK + kTileQ);  // K, Q (+ V, dO)
+    constexpr int kOutTile = 128 * kKeys * 2;  // a [128 queries][kKeys] bf16 tile of P (or dS) staged for the stores
+    static_assert((MODE == kBackward ? 2 : 1) * kOutTile <= (NW == 8 ? 3 : 2) * kStage, "the staged tiles reuse the stages");
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, l32 = lane & 31;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, uniform
@@ -207,13 +209,17 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) ld_scores_kernel(Lar
             const float lse2 = q_ok ? (MODE == kBackward ? p.LSE : p.LSEout)[(long)bh * p.n + q] * kLog2e
                                     : __builtin_inff();
             const float dl = (MODE == kBackward && q_ok) ? p.delta[(long)bh * p.n + q] : 0.f;
-            __bf16* prow = p.P + ((long)bh * p.npad + q) * p.npad;
-            __bf16* drow = p.dS + ((long)bh * p.npad + q) * p.npad;
+            // The tile goes to LDS first ([query][key] rows in the stages the k-loop has left) and from there to
+            // memory in whole rows: written straight from the accumulators, every store would touch 32 rows with 16
+            // bytes each.
+            char* prow = smem + (64 * wn + 32 * tn + l32) * (kKeys * 2);
 #pragma unroll
             for (int tm = 0; tm < 2; ++tm)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const int key = k0 + 64 * wm + 32 * tm + 8 * g + 4 * h;
+                    // 16-byte chunk of this row that holds keys 64 wm + 32 tm + 8 g .. + 7 (swizzled), half h
+                    const int slot = (((8 * wm + 4 * tm + g) ^ swz<kKeys>(64 * wn + 32 * tn + l32)) << 4) + 8 * h;
                     float pv[4], dv[4];
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
@@ -227,13 +233,27 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) ld_scores_kernel(Lar
                     u32x2 a;
                     a[0] = pack_bf16(pv[0], pv[1]);
                     a[1] = pack_bf16(pv[2], pv[3]);
-                    *reinterpret_cast<u32x2*>(prow + key) = a;
+                    *reinterpret_cast<u32x2*>(prow + slot) = a;
                     if (MODE == kBackward) {
                         a[0] = pack_bf16(dv[0], dv[1]);
                         a[1] = pack_bf16(dv[2], dv[3]);
-                        *reinterpret_cast<u32x2*>(drow + key) = a;
+                        *reinterpret_cast<u32x2*>(prow + kOutTile + slot) = a;
                     }
                 }
+        }
+    }
+    if (MODE != kStats) {
+        __syncthreads();
+        constexpr int kChunks = kKeys / 8, kRowsPerPass = kThreadsHere / kChunks;  // 16 rows per pass
+        const int cc = tid % kChunks;
+#pragma unroll
+        for (int r0 = 0; r0 < 128; r0 += kRowsPerPass) {
+            const int row = r0 + tid / kChunks;
+            const long off = ((long)bh * p.npad + q0 + row) * p.npad + k0 + 8 * cc;
+            *reinterpret_cast<u32x4*>(p.P + off) = *reinterpret_cast<const u32x4*>(smem + tile_off<kKeys>(row, cc));
+            if (MODE == kBackward)
+                *reinterpret_cast<u32x4*>(p.dS + off) =
+                    *reinterpret_cast<const u32x4*>(smem + kOutTile + tile_off<kKeys>(row, cc));
         }
     }
 }
