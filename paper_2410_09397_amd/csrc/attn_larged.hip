@@ -332,8 +332,8 @@ __global__ void __launch_bounds__(kThreads, 2) ld_gemm_kernel(LargeDParams p, Ge
     // Operand tiles go straight from global memory into the LDS stage that was last read one
     // step ago.  Rows of B past n repeat the last row; they meet columns (rows, if A is read
     // transposed) of A that are zero.  Lane offsets of the copies and of the fragment reads are
-    // computed once; the k-loop runs two steps per iteration so that the stage offsets are
-    // immediates (its trip count is a multiple of 8: all bounds are multiples of 256).
+    // computed once; the k-loop runs three steps per iteration so that the stage offsets are
+    // immediates.
     TileLoader<TM, BK> copy_at;   // A read transposed: BK rows of TM columns
     TileLoader<BK, TM> copy_a;    // A as stored: TM rows of BK columns
     TileLoader<128, BK> copy_b;
@@ -365,12 +365,21 @@ __global__ void __launch_bounds__(kThreads, 2) ld_gemm_kernel(LargeDParams p, Ge
 #pragma unroll
             for (int half = 0; half < 2; ++half) rb[t][half] = fb.tr(2 * wn + t, half) + kTileA;
     }
+    // Three stages: the copies of step k + 2 are issued while step k is multiplied, so two steps' worth of bytes
+    // (48 KB per workgroup) are in flight; with two stages the product kernels waited for memory at every step.
+    constexpr int kCopiesPerFetch = (kTileA + kTileB) / (1024 * 4);  // per wave
     fetch(k_begin, 0);
-    wait_direct_loads();
+    if (k_begin + BK < k_end) {
+        fetch(k_begin + BK, 1);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopiesPerFetch) : "memory");
+    } else {
+        wait_direct_loads();
+    }
     __syncthreads();
-    auto step = [&](int k, auto stage_off) {
-        constexpr int so = decltype(stage_off)::value;
-        if (k + BK < k_end) fetch(k + BK, so == 0 ? 1 : 0);
+    auto step = [&](int k, auto stage_index) {
+        constexpr int si = decltype(stage_index)::value, so = si * kStage;
+        const bool more = k + 2 * BK < k_end;
+        if (more) fetch(k + 2 * BK, (si + 2) % 3);
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
             bf16x8 a[4], b[2];
@@ -394,12 +403,20 @@ __global__ void __launch_bounds__(kThreads, 2) ld_gemm_kernel(LargeDParams p, Ge
 #pragma unroll
                 for (int tn = 0; tn < 2; ++tn) c[tm][tn] = mfma32(a[tm], b[tn], c[tm][tn]);
         }
-        wait_direct_loads();
+        // step k + 1 must have landed; the copies just issued may stay in flight
+        if (more) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopiesPerFetch) : "memory");
+        else wait_direct_loads();
         __syncthreads();
     };
-    for (int k = k_begin; k < k_end; k += 2 * BK) {
+    int k = k_begin;
+    for (; k + 3 * BK <= k_end; k += 3 * BK) {
         step(k, std::integral_constant<int, 0>{});
-        step(k + BK, std::integral_constant<int, kStage>{});
+        step(k + BK, std::integral_constant<int, 1>{});
+        step(k + 2 * BK, std::integral_constant<int, 2>{});
+    }
+    if (k < k_end) {
+        step(k, std::integral_constant<int, 0>{});
+        if (k + BK < k_end) step(k + BK, std::integral_constant<int, 1>{});
     }
     // accumulator: lane <-> output column, register <-> output row
 #pragma unroll
@@ -419,7 +436,7 @@ static hipError_t set_lds(const void* fn, int bytes) {
     return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
 }
 
-constexpr int kGemmLds = 2 * (kGemmM + 128) * kGemmBK * 2;  // two stages of an A and a B tile
+constexpr int kGemmLds = 3 * (kGemmM + 128) * kGemmBK * 2;  // three stages of an A and a B tile (72 KB: two workgroups per CU)
 template <bool A_KMAJOR>
 static void run_gemm(const LargeDParams& p, const __bf16* A, const __bf16* B, __bf16* C, float alpha,
                      hipStream_t stream) {
