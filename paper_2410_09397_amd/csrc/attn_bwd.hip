@@ -517,12 +517,15 @@ __global__ void __launch_bounds__(kThreads, D == 64 ? 4 : (QT == 1 && D <= 128 ?
         settle(dl[t]);
     }
     // -delta of this lane's query in all 16 registers of an accumulator block: the dP^T chains start
-    // from it (C operand of their first MFMA), so dP^T - delta costs no vector instruction per tile
+    // from it (C operand of their first MFMA), so dP^T - delta costs no vector instruction per tile.
+    // Not at d = 64: there the kernel is built for four workgroups per CU (128 registers) and the
+    // 16 extra registers would spill (measured: 12 -> 332 bytes of scratch per lane, four times slower).
+    constexpr bool kDeltaInAcc = D >= 128;
     f32x16 ndl[QT];
 #pragma unroll
     for (int t = 0; t < QT; ++t) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) ndl[t][i] = -dl[t];
+        for (int i = 0; i < 16; ++i) ndl[t][i] = kDeltaInAcc ? -dl[t] : 0.f;
     }
     FragOffsets<D> lane_offsets;
     lane_offsets.init(lane);
@@ -571,7 +574,7 @@ __global__ void __launch_bounds__(kThreads, D == 64 ? 4 : (QT == 1 && D <= 128 ?
                 for (int i = 0; i < 16; ++i) {
                     float pv = __builtin_amdgcn_exp2f(st[t][i] * c - lse2[t]);
                     if constexpr (decltype(masked)::value) pv = (8 * (i >> 2) + (i & 3) > lim) ? 0.f : pv;
-                    dpt[t][i] = pv * dpt[t][i];
+                    dpt[t][i] = kDeltaInAcc ? pv * dpt[t][i] : pv * (dpt[t][i] - dl[t]);
                 }
 #pragma unroll
                 for (int ss = 0; ss < 2; ++ss) dsb[t][ss] = acc_to_operand(dpt[t], ss);

@@ -200,17 +200,24 @@ def main():
 
 
 # ------------------------------------------------------------------ compiler resource usage
-def resources_main():
-    """python -m paper_2410_09397_amd.pmc_summary resources  -> markdown table of registers, scratch and
-    occupancy of every kernel, from hipcc -Rpass-analysis=kernel-resource-usage on the committed sources."""
+def kernel_resources(sources=None):
+    """Registers, scratch and occupancy of every kernel in the given sources (default: all of the library's), from
+    hipcc -Rpass-analysis=kernel-resource-usage: a list of dicts with the compiler's field names plus "kernel"."""
     import re
     import subprocess
+    from concurrent.futures import ThreadPoolExecutor
     from paper_2410_09397_amd import build as hip_build
-    rows = []
-    for src in hip_build.SOURCES:
+
+    def one(src):
         cmd = ["hipcc", *hip_build.FLAGS, "-Rpass-analysis=kernel-resource-usage", "-c",
                os.path.join(hip_build.CSRC, src), "-o", os.devnull]
-        err = subprocess.run(cmd, capture_output=True, text=True).stderr
+        return subprocess.run(cmd, capture_output=True, text=True).stderr
+
+    srcs = list(sources or hip_build.SOURCES)
+    with ThreadPoolExecutor(max_workers=4) as pool:
+        outputs = list(pool.map(one, srcs))
+    rows = []
+    for err in outputs:
         cur = None
         for line in err.splitlines():
             m = re.search(r"remark: (?:Function Name: (\S+)|\s+(\S[^:]*): (\S+))", line)
@@ -224,6 +231,13 @@ def resources_main():
                 rows.append(cur)
             elif cur is not None:
                 cur[m.group(2).strip()] = m.group(3)
+    return rows
+
+
+def resources_main():
+    """python -m paper_2410_09397_amd.pmc_summary resources  -> markdown table of registers, scratch and
+    occupancy of every kernel, from hipcc -Rpass-analysis=kernel-resource-usage on the committed sources."""
+    rows = kernel_resources()
     print("## Compiler resource usage (`hipcc -Rpass-analysis=kernel-resource-usage`, gfx950)\n")
     print("| kernel | VGPRs | AGPRs | scratch (bytes/lane) | occupancy (waves/SIMD) |")
     print("|---|---|---|---|---|")
