@@ -8,6 +8,7 @@ timed steps, measured with HIP events on the launch stream; ms_per_step covers f
 backward.  Prints one JSON line.
 """
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -123,6 +124,8 @@ def main():
                                                   "the JSON line then names the derived workload")
     ap.add_argument("--extra-frac", type=float, default=None,
                     help="block-sparse workload only: share of non-diagonal key blocks kept per query-block row")
+    ap.add_argument("--per-head-masks", action="store_true",
+                    help="block-sparse workload: a different block mask for every (batch, head) pair (sweeps)")
     ap.add_argument("--tiling", type=int, default=0,
                     help="attn_bwd_tiling of include/attn_mi355x.h (0 = the library's choice, 1 = two kernels, "
                          "2 / 3 = one pass with 64 / 128 keys per workgroup, 6 = four-phase scheme, 7 = fused split-d)")
@@ -165,6 +168,10 @@ def main():
         w = synth.reshaped(w, args.shape)
     if args.extra_frac is not None:
         w = synth.with_density(w, args.extra_frac)
+    if args.per_head_masks:
+        if not w.sparse:
+            sys.exit("--per-head-masks applies to the block-sparse workload")
+        w = dataclasses.replace(w, name=w.name + "_masks_per_head", per_head_masks=True)
     dt = {"bf16": torch.bfloat16, "f32": torch.float32}[w.dtype]
     inp = synth.make_inputs(w)
     Q, K, V, dO = (torch.from_numpy(inp[t]).to("cuda").to(dt) for t in ("Q", "K", "V", "dO"))
@@ -303,7 +310,7 @@ def main():
         out["wgrad"] = {"ms": ms, "algorithmic_tflops": flops / (ms * 1e-3) * 1e-12,
                         "note": "projections + forward + dQ kernel + A_1^T dQ; executes 10 n^2 d per pair"}
     if args.other_workloads is None:  # by default only beside the plain default run
-        args.other_workloads = (args.workload == 3 and not args.shape and args.extra_frac is None and not args.tiling
+        args.other_workloads = (args.workload == 3 and not args.shape and args.extra_frac is None and not args.tiling and not args.per_head_masks
                                 and not args.zero_operands and not args.calibrate_copy and not args.no_kernel_split)
     if args.other_workloads:
         out["other_workloads"] = [quick_workload(i) for i in (1, 2, 4, 5) if i != args.workload]
