@@ -3,9 +3,9 @@
 // four-phase small-cache algorithm of App. C: square tiles with the contraction loop split
 // into chunks, and the n x n matrices f (here P) and p (here dS) written to memory between
 // the phases:
-//   scores kernel : S^T = K Q^T and dP^T = V dO^T tile by tile with a k-loop over d-chunks
-//                   (phases 1 and 2), then f = exp(S - LSE) and p = f o (q - v) in the epilogue
-//                   (phase 3, one sweep because v = rowsum(dO o O) is precomputed) -> P, dS in HBM
+//   scores kernel : per tile S^T = K Q^T with a k-loop over d-chunks, f = exp(S - LSE); then dP^T = V dO^T
+//                   with a second k-loop and p = f o (q - v) (phases 1 to 3; one sweep over the tile
+//                   because v = rowsum(dO o O) is precomputed) -> P, dS in HBM
 //   gemm kernel   : dV = P^T dO, dK = scale dS^T Q, dQ = scale dS K as tiled products with the
 //                   k-loop over n (phase 4 written for dQ/dK/dV instead of A_1^T p A_2)
 // The forward uses the same kernels: partial row statistics of S per 64-key chunk, a combine
@@ -30,20 +30,19 @@ __device__ __forceinline__ void zero_acc(f32x16 (&c)[2][2]) {
 
 }  // namespace
 
-enum ScoreMode { kStats = 0, kProbs = 1, kBackward = 2 };
+enum ScoreMode { kStats = 0, kProbs = 1 };
 
-// One workgroup of NW waves: a (32 NW keys) x (128 queries) tile of S^T (and dP^T), waves in an
+// Forward scores kernel.  One workgroup of NW waves: a (32 NW keys) x (128 queries) tile of S^T, waves in an
 // (NW / 2) x 2 grid of 64 x 64 sub-tiles.  Accumulator: lane <-> query, register <-> key.
-// The forward modes run 8 waves on 256 x 128 tiles with three LDS stages (fewer bytes copied per
-// MFMA; 10 % faster there), the backward mode 4 waves on 128 x 128 tiles with two stages and two
-// workgroups per CU (the 8-wave shape measured 15 % slower for it).
+// Both modes run 8 waves on 256 x 128 tiles with three LDS stages (fewer bytes copied per MFMA than with
+// 128 x 128 tiles; 10 % faster).
 template <int MODE, int NW>
 __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) ld_scores_kernel(LargeDParams p) {
     constexpr int BK = 32, kKeys = 32 * NW, kThreadsHere = 64 * NW;
     constexpr int kTileK = kKeys * BK * 2, kTileQ = 128 * BK * 2;  // bytes per operand tile
-    constexpr int kStage = (MODE == kBackward ? 2 : 1) * (kTileK + kTileQ);  // K, Q (+ V, dO)
-    constexpr int kOutTile = 128 * kKeys * 2;  // a [128 queries][kKeys] bf16 tile of P (or dS) staged for the stores
-    static_assert((MODE == kBackward ? 2 : 1) * kOutTile <= (NW == 8 ? 3 : 2) * kStage, "the staged tiles reuse the stages");
+    constexpr int kStage = kTileK + kTileQ;  // K, Q
+    constexpr int kOutTile = 128 * kKeys * 2;  // a [128 queries][kKeys] bf16 tile of P staged for the stores
+    static_assert(kOutTile <= (NW == 8 ? 3 : 2) * kStage, "the staged tile reuses the stages");
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, l32 = lane & 31;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, uniform
@@ -79,7 +78,6 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) ld_scores_kernel(Lar
             for (int e = threadIdx.x; e < 128 * 16; e += kThreadsHere) {
                 const long off = ((long)bh * p.npad + qb * 128 + e / 16) * p.npad + kb * 128 + (e % 16) * 8;
                 *reinterpret_cast<u32x4*>(p.P + off) = z;
-                if (MODE == kBackward) *reinterpret_cast<u32x4*>(p.dS + off) = z;
             }
         }
         return;
@@ -88,17 +86,14 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) ld_scores_kernel(Lar
     const int k0 = kb * kKeys, q0 = qb * 128;
     const __bf16* gK = p.K + base;
     const __bf16* gQ = p.Q + base;
-    const __bf16* gV = (MODE == kBackward ? p.V : p.K) + base;
-    const __bf16* gG = (MODE == kBackward ? p.dO : p.Q) + base;
     const long ld = p.stride_n;
 
-    f32x16 s[2][2], dp[2][2];
+    f32x16 s[2][2];
     zero_acc(s);
-    if (MODE == kBackward) zero_acc(dp);
 
     // Operand chunks (kKeys or 128 rows x BK columns) go straight from global memory into the LDS
     // stage that was last read one chunk ago; rows past n repeat the last row and are masked in
-    // the epilogue.  Stage layout: [K][Q]([V][dO]).  Lane offsets of the copies and of the
+    // the epilogue.  Stage layout: [K][Q].  Lane offsets of the copies and of the
     // fragment reads are computed once: the loop itself has no address arithmetic.
     TileLoader<BK, kKeys, NW> copy_k;
     TileLoader<BK, 128, NW> copy_q;
@@ -108,10 +103,6 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) ld_scores_kernel(Lar
         char* b = smem + stage * kStage;
         copy_k.load(gK + c0, ld, k0, p.n, b, tid);
         copy_q.load(gQ + c0, ld, q0, p.n, b + kTileK, tid);
-        if (MODE == kBackward) {
-            copy_k.load(gV + c0, ld, k0, p.n, b + kTileK + kTileQ, tid);
-            copy_q.load(gG + c0, ld, q0, p.n, b + 2 * kTileK + kTileQ, tid);
-        }
     };
     // fragment of rows row0 + 32 t + l32, k-step ks: register + 32 t row pitches + stage offset
     int rk[BK / 16], rq[BK / 16];
@@ -123,7 +114,7 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) ld_scores_kernel(Lar
     // kStages LDS stages: the copy of chunk kc + kStages - 1 is issued while chunk kc is multiplied
     // (with one workgroup per CU nothing else hides the copies' latency: three stages there).
     constexpr int kStages = NW == 8 ? 3 : 2, kAhead = kStages - 1;
-    constexpr int kCopiesPerFetch = (MODE == kBackward ? 2 : 1) * (kTileK + kTileQ) / (1024 * NW);  // per wave
+    constexpr int kCopiesPerFetch = (kTileK + kTileQ) / (1024 * NW);  // per wave
     const int chunks = p.d / BK;
     for (int c = 0; c < kAhead && c < chunks; ++c) fetch(c * BK, c);
     wait_direct_loads();
@@ -144,17 +135,6 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) ld_scores_kernel(Lar
             for (int tm = 0; tm < 2; ++tm)
 #pragma unroll
                 for (int tn = 0; tn < 2; ++tn) s[tm][tn] = mfma32(a[tm], q[tn], s[tm][tn]);
-            if (MODE == kBackward) {
-#pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    a[t] = FragOffsets<BK>::read(smem, rk[ks], so + kTileK + kTileQ + 32 * t * (BK * 2));
-                    q[t] = FragOffsets<BK>::read(smem, rq[ks], so + kTileK + kTileQ + 32 * t * (BK * 2));
-                }
-#pragma unroll
-                for (int tm = 0; tm < 2; ++tm)
-#pragma unroll
-                    for (int tn = 0; tn < 2; ++tn) dp[tm][tn] = mfma32(a[tm], q[tn], dp[tm][tn]);
-            }
         }
         // chunk kc + 1 must have landed; with three stages the copies just issued may stay in flight
         if (more && kStages == 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopiesPerFetch) : "memory");
@@ -206,9 +186,7 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) ld_scores_kernel(Lar
                 p.stat_l[o] = sum;
             }
         } else {
-            const float lse2 = q_ok ? (MODE == kBackward ? p.LSE : p.LSEout)[(long)bh * p.n + q] * kLog2e
-                                    : __builtin_inff();
-            const float dl = (MODE == kBackward && q_ok) ? p.delta[(long)bh * p.n + q] : 0.f;
+            const float lse2 = q_ok ? p.LSEout[(long)bh * p.n + q] * kLog2e : __builtin_inff();
             // The tile goes to LDS first ([query][key] rows in the stages the k-loop has left) and from there to
             // memory in whole rows: written straight from the accumulators, every store would touch 32 rows with 16
             // bytes each.
@@ -220,7 +198,7 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) ld_scores_kernel(Lar
                     const int key = k0 + 64 * wm + 32 * tm + 8 * g + 4 * h;
                     // 16-byte chunk of this row that holds keys 64 wm + 32 tm + 8 g .. + 7 (swizzled), half h
                     const int slot = (((8 * wm + 4 * tm + g) ^ swz<kKeys>(64 * wn + 32 * tn + l32)) << 4) + 8 * h;
-                    float pv[4], dv[4];
+                    float pv[4];
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         float v = __builtin_amdgcn_exp2f(s[tm][tn][4 * g + r] * c - lse2);
@@ -228,17 +206,11 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) ld_scores_kernel(Lar
                         if (lse2 == -__builtin_inff()) v = 0.f;
                         if (need_mask && (key + r >= p.n || (p.causal && key + r > q))) v = 0.f;
                         pv[r] = v;
-                        if (MODE == kBackward) dv[r] = v * (dp[tm][tn][4 * g + r] - dl);
                     }
                     u32x2 a;
                     a[0] = pack_bf16(pv[0], pv[1]);
                     a[1] = pack_bf16(pv[2], pv[3]);
                     *reinterpret_cast<u32x2*>(prow + slot) = a;
-                    if (MODE == kBackward) {
-                        a[0] = pack_bf16(dv[0], dv[1]);
-                        a[1] = pack_bf16(dv[2], dv[3]);
-                        *reinterpret_cast<u32x2*>(prow + kOutTile + slot) = a;
-                    }
                 }
         }
     }
@@ -251,11 +223,198 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) ld_scores_kernel(Lar
             const int row = r0 + tid / kChunks;
             const long off = ((long)bh * p.npad + q0 + row) * p.npad + k0 + 8 * cc;
             *reinterpret_cast<u32x4*>(p.P + off) = *reinterpret_cast<const u32x4*>(smem + tile_off<kKeys>(row, cc));
-            if (MODE == kBackward)
-                *reinterpret_cast<u32x4*>(p.dS + off) =
-                    *reinterpret_cast<const u32x4*>(smem + kOutTile + tile_off<kKeys>(row, cc));
         }
     }
+}
+
+// Backward scores kernel: P and dS tiles of 128 queries x 256 keys.  The two products of a tile are formed one after the
+// other - S^T over all of d, then dP^T over all of d - so that a wave can hold a 128 x 64 block (4 x 2 accumulators) of
+// the one in progress: 256 x 128 tiles with four waves move 384 bytes from memory per MFMA instead of the 512 of
+// 128 x 128 tiles, a k-step needs the chunks of two operands only (24 KB), and three LDS stages (copies two steps ahead)
+// fit two workgroups on a CU.  Between the passes P stays in registers, rounded to bf16 as it is stored
+// (dS = P (dP - delta) is formed from that rounded P).  Accumulator: lane <-> query, register <-> key.
+constexpr int kScoreBwdStage = (256 + 128) * 32 * 2, kScoreLdsBwd2 = 3 * kScoreBwdStage;
+__global__ void __launch_bounds__(kThreads, 2) ld_scores_bwd_kernel(LargeDParams p) {
+    constexpr int BK = 32, kKeys = 256;
+    constexpr int kTileK = kKeys * BK * 2, kTileQ = 128 * BK * 2, kStage = kScoreBwdStage;
+    constexpr int kOutTile = 128 * kKeys * 2;  // a [128 queries][256 keys] bf16 tile staged for the stores
+    static_assert(kOutTile <= 3 * kStage, "the staged tile reuses the stages");
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, l32 = lane & 31;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = w >> 1, wn = w & 1;  // keys 128 wm .., queries 64 wn ..
+    const int nbq = p.npad / 128, nbk = p.npad / kKeys;
+    int bh, kb, qb;
+    {   // XCD-contiguous tile order, regions of 8 query tiles x 1024 keys (as in the forward modes)
+        constexpr int kPerRegionRow = 1024 / kKeys;
+        const int per_head = nbq * nbk, total = per_head * p.batch * p.heads;
+        int t = blockIdx.x;
+        if ((total & 7) == 0) t = (t >> 3) + (t & 7) * (total >> 3);
+        bh = t / per_head;
+        const int tile = t % per_head;
+        if ((nbq & 7) == 0 && nbk % kPerRegionRow == 0) {
+            const int region = tile / (8 * kPerRegionRow), in = tile % (8 * kPerRegionRow);
+            const int rpr = nbk / kPerRegionRow;
+            qb = (region / rpr) * 8 + in / kPerRegionRow;
+            kb = (region % rpr) * kPerRegionRow + in % kPerRegionRow;
+        } else {
+            qb = tile / nbk;
+            kb = tile % nbk;
+        }
+    }
+    if (p.causal && kb * kKeys > qb * 128 + 127) return;  // wholly above the diagonal: never read
+    const long base = (long)(bh / p.heads) * p.stride_b + (long)(bh % p.heads) * p.stride_h;
+    const int k0 = kb * kKeys, q0 = qb * 128;
+    const long ld = p.stride_n;
+
+    TileLoader<BK, kKeys, 4> copy_k;
+    TileLoader<BK, 128, 4> copy_q;
+    copy_k.init(tid, ld);
+    copy_q.init(tid, ld);
+    constexpr int kCopiesPerFetch = (kTileK + kTileQ) / (1024 * 4);  // per wave
+    int rk[BK / 16], rq[BK / 16];
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+        rk[ks] = tile_off<BK>(128 * wm + l32, 2 * ks + h);
+        rq[ks] = tile_off<BK>(64 * wn + l32, 2 * ks + h) + kTileK;
+    }
+    const int chunks = p.d / BK;
+
+    f32x16 c[4][2];
+    // one product over all of d: rows of gA (keys) x rows of gB (queries), three stages
+    auto product = [&](const __bf16* gA, const __bf16* gB) {
+#pragma unroll
+        for (int tm = 0; tm < 4; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) c[tm][tn][i] = 0.f;
+        auto fetch = [&](int kc, int stage) {
+            char* b = smem + stage * kStage;
+            copy_k.load(gA + kc * BK, ld, k0, p.n, b, tid);
+            copy_q.load(gB + kc * BK, ld, q0, p.n, b + kTileK, tid);
+        };
+        fetch(0, 0);
+        if (chunks > 1) {
+            fetch(1, 1);
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopiesPerFetch) : "memory");
+        } else {
+            wait_direct_loads();
+        }
+        __syncthreads();
+        auto step = [&](int kc, auto stage_index) {
+            constexpr int si = decltype(stage_index)::value, so = si * kStage;
+            const bool more = kc + 2 < chunks;
+            if (more) fetch(kc + 2, (si + 2) % 3);
+#pragma unroll
+            for (int ks = 0; ks < BK / 16; ++ks) {
+                // the key fragments one ahead of their MFMAs, two live at a time (the accumulators and the packed P of
+                // the first pass leave room for little else)
+                bf16x8 b[2], a = FragOffsets<BK>::read(smem, rk[ks], so);
+#pragma unroll
+                for (int t = 0; t < 2; ++t) b[t] = FragOffsets<BK>::read(smem, rq[ks], so + 32 * t * (BK * 2));
+#pragma unroll
+                for (int tm = 0; tm < 4; ++tm) {
+                    bf16x8 a_next = a;
+                    if (tm + 1 < 4) a_next = FragOffsets<BK>::read(smem, rk[ks], so + 32 * (tm + 1) * (BK * 2));
+#pragma unroll
+                    for (int tn = 0; tn < 2; ++tn) c[tm][tn] = mfma32(a, b[tn], c[tm][tn]);
+                    a = a_next;
+                }
+            }
+            if (more) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopiesPerFetch) : "memory");
+            else wait_direct_loads();
+            __syncthreads();
+        };
+        int kc = 0;
+        for (; kc + 3 <= chunks; kc += 3) {
+            step(kc, std::integral_constant<int, 0>{});
+            step(kc + 1, std::integral_constant<int, 1>{});
+            step(kc + 2, std::integral_constant<int, 2>{});
+        }
+        if (kc < chunks) {
+            step(kc, std::integral_constant<int, 0>{});
+            if (kc + 1 < chunks) step(kc + 1, std::integral_constant<int, 1>{});
+        }
+    };
+    // the whole tile from LDS ([query][key] rows, swizzled chunks) to a matrix in the workspace, in whole rows
+    auto store_tile = [&](__bf16* M) {
+        __syncthreads();
+        constexpr int kChunks = kKeys / 8, kRowsPerPass = kThreads / kChunks;  // 8 rows per pass
+        const int cc = tid % kChunks;
+        // the lane's addresses are formed here, not carried in registers through the product loop in front
+        int q_first = q0;
+        asm volatile("" : "+s"(q_first));
+#pragma unroll 4
+        for (int r0 = 0; r0 < 128; r0 += kRowsPerPass) {
+            const int row = r0 + tid / kChunks;
+            const long off = ((long)bh * p.npad + q_first + row) * p.npad + k0 + 8 * cc;
+            *reinterpret_cast<u32x4*>(M + off) = *reinterpret_cast<const u32x4*>(smem + tile_off<kKeys>(row, cc));
+        }
+        __syncthreads();  // the stages are free again
+    };
+
+    // ---- pass 1: S^T -> P (bf16, kept packed in registers and written out)
+    product(p.K + base, p.Q + base);
+    const float cs = p.scale * kLog2e;
+    const bool need_mask = (p.causal && k0 + kKeys - 1 > q0) || (k0 + kKeys > p.n);
+    uint32_t pk[4][2][8];
+#pragma unroll
+    for (int tn = 0; tn < 2; ++tn) {
+        const int q = q0 + 64 * wn + 32 * tn + l32;
+        const bool q_ok = q < p.n;
+        const float lse2 = q_ok ? p.LSE[(long)bh * p.n + q] * kLog2e : __builtin_inff();
+        char* prow = smem + (64 * wn + 32 * tn + l32) * (kKeys * 2);
+#pragma unroll
+        for (int tm = 0; tm < 4; ++tm)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int key = k0 + 128 * wm + 32 * tm + 8 * g + 4 * h;
+                float pv[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    float v = __builtin_amdgcn_exp2f(c[tm][tn][4 * g + r] * cs - lse2);
+                    if (lse2 == -__builtin_inff()) v = 0.f;  // a fully masked row has LSE = -inf
+                    if (need_mask && (key + r >= p.n || (p.causal && key + r > q))) v = 0.f;
+                    pv[r] = v;
+                }
+                u32x2 a;
+                a[0] = pack_bf16(pv[0], pv[1]);
+                a[1] = pack_bf16(pv[2], pv[3]);
+                pk[tm][tn][2 * g] = a[0];
+                pk[tm][tn][2 * g + 1] = a[1];
+                const int slot = (((16 * wm + 4 * tm + g) ^ swz<kKeys>(64 * wn + 32 * tn + l32)) << 4) + 8 * h;
+                *reinterpret_cast<u32x2*>(prow + slot) = a;
+            }
+    }
+    store_tile(p.P);
+
+    // ---- pass 2: dP^T -> dS = P (dP - delta)
+    product(p.V + base, p.dO + base);
+#pragma unroll
+    for (int tn = 0; tn < 2; ++tn) {
+        const int q = q0 + 64 * wn + 32 * tn + l32;
+        const float dl = q < p.n ? p.delta[(long)bh * p.n + q] : 0.f;  // (P is 0 in rows past n)
+        char* prow = smem + (64 * wn + 32 * tn + l32) * (kKeys * 2);
+#pragma unroll
+        for (int tm = 0; tm < 4; ++tm)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                float dv[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const uint32_t word = pk[tm][tn][2 * g + (r >> 1)];
+                    const float pv = __builtin_bit_cast(float, (r & 1) ? (word & 0xffff0000u) : (word << 16));
+                    dv[r] = pv * (c[tm][tn][4 * g + r] - dl);
+                }
+                u32x2 a;
+                a[0] = pack_bf16(dv[0], dv[1]);
+                a[1] = pack_bf16(dv[2], dv[3]);
+                const int slot = (((16 * wm + 4 * tm + g) ^ swz<kKeys>(64 * wn + 32 * tn + l32)) << 4) + 8 * h;
+                *reinterpret_cast<u32x2*>(prow + slot) = a;
+            }
+    }
+    store_tile(p.dS);
 }
 
 // LSE from the per-chunk statistics: one thread per row.
@@ -446,12 +605,11 @@ static void run_gemm(const LargeDParams& p, const __bf16* A, const __bf16* B, __
 }
 
 constexpr int kScoreLdsFwd = 3 * (256 + 128) * 32 * 2;      // 8 waves: three stages of a K and a Q chunk
-constexpr int kScoreLdsBwd = 2 * 2 * (128 + 128) * 32 * 2;  // 4 waves: two stages of K, Q, V, dO chunks
 // LDS sizes of the large-d kernels on the current device (set on every call: cheap, and per device).
 hipError_t configure_larged() {
     hipError_t e = set_lds(reinterpret_cast<const void*>(ld_scores_kernel<kStats, 8>), kScoreLdsFwd);
     if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_scores_kernel<kProbs, 8>), kScoreLdsFwd);
-    if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_scores_kernel<kBackward, 4>), kScoreLdsBwd);
+    if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_scores_bwd_kernel), kScoreLdsBwd2);
     if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_gemm_kernel<true>), kGemmLds);
     if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_gemm_kernel<false>), kGemmLds);
     return e;
@@ -463,7 +621,7 @@ hipError_t launch_larged(bool backward, const LargeDParams& p, hipStream_t strea
     const unsigned bh = (unsigned)(p.batch * p.heads);
     const unsigned nbq = (unsigned)(p.npad / 128);
     const dim3 fgrid(nbq * (unsigned)(p.npad / 256) * bh), fblock(512);  // forward modes: 256-key tiles, 8 waves
-    const dim3 bgrid(nbq * nbq * bh), block(kThreads);                   // backward mode: 128-key tiles, 4 waves
+    const dim3 block(kThreads);
     if (!backward) {
         hipLaunchKernelGGL((ld_scores_kernel<kStats, 8>), fgrid, fblock, kScoreLdsFwd, stream, p);
         const long rows = (long)bh * p.n;
@@ -471,7 +629,7 @@ hipError_t launch_larged(bool backward, const LargeDParams& p, hipStream_t strea
         hipLaunchKernelGGL((ld_scores_kernel<kProbs, 8>), fgrid, fblock, kScoreLdsFwd, stream, p);
         run_gemm<false>(p, p.P, p.V, p.Oout, 1.f, stream);
     } else {
-        hipLaunchKernelGGL((ld_scores_kernel<kBackward, 4>), bgrid, block, kScoreLdsBwd, stream, p);
+        hipLaunchKernelGGL(ld_scores_bwd_kernel, dim3(nbq * (unsigned)(p.npad / 256) * bh), block, kScoreLdsBwd2, stream, p);
         run_gemm<true>(p, p.P, p.dO, p.dV, 1.f, stream);
         run_gemm<true>(p, p.dS, p.Q, p.dK, p.scale, stream);
         run_gemm<false>(p, p.dS, p.K, p.dQ, p.scale, stream);

@@ -117,22 +117,22 @@ def split_d(n, d, causal=False, es=2, block=32):
     return out
 
 
-def four_phase(n, d, causal=False, es=2, score_tile=128, prod_m=256, prod_n=128):
+def four_phase(n, d, causal=False, es=2, score_q=128, score_k=256, prod_m=256, prod_n=128):
     """Bytes per head of the four-phase path: the row-sum kernel, the score kernel (tiles of 128 queries x
-    128 keys with a k-loop over d, f and p written as n x n bf16 matrices, n padded to 256) and the
-    three products with a k-loop over n (tiles of 256 x 128 outputs)."""
+    256 keys, S and then dP with a k-loop over d each, f and p written as n x n bf16 matrices, n padded to 256)
+    and the three products with a k-loop over n (tiles of 256 x 128 outputs)."""
     npad = _ceil(n, 256) * 256
     rd = 2 * n * d * es
     wr = n * 4
     tiles = 0
-    for i0 in range(0, npad, score_tile):
-        for j0 in range(0, npad, score_tile):
-            if causal and j0 > i0 + score_tile - 1:
+    for i0 in range(0, npad, score_q):
+        for j0 in range(0, npad, score_k):
+            if causal and j0 > i0 + score_q - 1:
                 continue
             tiles += 1
-    rd += tiles * (4 * score_tile * d * es + 2 * score_tile * 4)   # Q, dO, K, V chunks of the tile; LSE, v
-    wr += tiles * 2 * score_tile * score_tile * es                 # f, p
-    streamed = tiles * 4 * score_tile * d * es
+    rd += tiles * (2 * (score_q + score_k) * d * es + 2 * score_q * 4)   # Q, dO, K, V chunks of the tile; LSE, v
+    wr += tiles * 2 * score_q * score_k * es                             # f, p
+    streamed = tiles * 2 * (score_q + score_k) * d * es
     for _ in range(3):                                             # dV = f^T dO, dK = p^T Q, dQ = p K
         out_tiles = _ceil(npad, prod_m) * _ceil(d, prod_n)
         k_len = npad * (0.5 if causal else 1.0)                    # the invisible half of f / p is skipped
