@@ -17,226 +17,21 @@
 
 namespace attn {
 
-namespace {
-
-__device__ __forceinline__ void zero_acc(f32x16 (&c)[2][2]) {
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) c[a][b][i] = 0.f;
-}
-
-}  // namespace
-
-enum ScoreMode { kStats = 0, kProbs = 1 };
-
-// Forward scores kernel.  One workgroup of NW waves: a (32 NW keys) x (128 queries) tile of S^T, waves in an
-// (NW / 2) x 2 grid of 64 x 64 sub-tiles.  Accumulator: lane <-> query, register <-> key.
-// Both modes run 8 waves on 256 x 128 tiles with three LDS stages (fewer bytes copied per MFMA than with
-// 128 x 128 tiles; 10 % faster).
-template <int MODE, int NW>
-__global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) ld_scores_kernel(LargeDParams p) {
-    constexpr int BK = 32, kKeys = 32 * NW, kThreadsHere = 64 * NW;
-    constexpr int kTileK = kKeys * BK * 2, kTileQ = 128 * BK * 2;  // bytes per operand tile
-    constexpr int kStage = kTileK + kTileQ;  // K, Q
-    constexpr int kOutTile = 128 * kKeys * 2;  // a [128 queries][kKeys] bf16 tile of P staged for the stores
-    static_assert(kOutTile <= (NW == 8 ? 3 : 2) * kStage, "the staged tile reuses the stages");
-    extern __shared__ __attribute__((aligned(1024))) char smem[];
-    const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, l32 = lane & 31;
-    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, uniform
-    const int wm = w >> 1, wn = w & 1;
-    const int nbq = p.npad / 128, nbk = p.npad / kKeys;
-    // 1-D grid; ids congruent mod 8 share an XCD and its 4 MB L2.  Each XCD gets a contiguous
-    // range of tiles, ordered so that consecutive ones form a block of 8 query tiles x 1024 keys:
-    // their operand blocks (4 MB at d = 512) are what the L2 can keep.
-    int bh, kb, qb;
-    {
-        constexpr int kPerRegionRow = 1024 / kKeys;  // key tiles per region row: 8 or 4
-        const int per_head = nbq * nbk, total = per_head * p.batch * p.heads;
-        int t = blockIdx.x;
-        if ((total & 7) == 0) t = (t >> 3) + (t & 7) * (total >> 3);
-        bh = t / per_head;
-        const int tile = t % per_head;
-        if ((nbq & 7) == 0 && nbk % kPerRegionRow == 0) {
-            const int region = tile / (8 * kPerRegionRow), in = tile % (8 * kPerRegionRow);
-            const int rpr = nbk / kPerRegionRow;  // regions per row
-            qb = (region / rpr) * 8 + in / kPerRegionRow;
-            kb = (region % rpr) * kPerRegionRow + in % kPerRegionRow;
-        } else {
-            qb = tile / nbk;
-            kb = tile % nbk;
-        }
-    }
-    if (p.causal && kb * kKeys > qb * 128 + 127) {
-        // Whole tile above the diagonal.  The product kernels work on 256-row blocks of P and dS:
-        // with 128-key tiles the tile next to the diagonal tile of an even query block is read
-        // there and is zeroed here; every other tile above the diagonal is never read.
-        if (kKeys == 128 && MODE != kStats && kb == (qb | 1)) {
-            const u32x4 z = {0, 0, 0, 0};
-            for (int e = threadIdx.x; e < 128 * 16; e += kThreadsHere) {
-                const long off = ((long)bh * p.npad + qb * 128 + e / 16) * p.npad + kb * 128 + (e % 16) * 8;
-                *reinterpret_cast<u32x4*>(p.P + off) = z;
-            }
-        }
-        return;
-    }
-    const long base = (long)(bh / p.heads) * p.stride_b + (long)(bh % p.heads) * p.stride_h;
-    const int k0 = kb * kKeys, q0 = qb * 128;
-    const __bf16* gK = p.K + base;
-    const __bf16* gQ = p.Q + base;
-    const long ld = p.stride_n;
-
-    f32x16 s[2][2];
-    zero_acc(s);
-
-    // Operand chunks (kKeys or 128 rows x BK columns) go straight from global memory into the LDS
-    // stage that was last read one chunk ago; rows past n repeat the last row and are masked in
-    // the epilogue.  Stage layout: [K][Q].  Lane offsets of the copies and of the
-    // fragment reads are computed once: the loop itself has no address arithmetic.
-    TileLoader<BK, kKeys, NW> copy_k;
-    TileLoader<BK, 128, NW> copy_q;
-    copy_k.init(tid, ld);
-    copy_q.init(tid, ld);
-    auto fetch = [&](int c0, int stage) {
-        char* b = smem + stage * kStage;
-        copy_k.load(gK + c0, ld, k0, p.n, b, tid);
-        copy_q.load(gQ + c0, ld, q0, p.n, b + kTileK, tid);
-    };
-    // fragment of rows row0 + 32 t + l32, k-step ks: register + 32 t row pitches + stage offset
-    int rk[BK / 16], rq[BK / 16];
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-        rk[ks] = tile_off<BK>(64 * wm + l32, 2 * ks + h);
-        rq[ks] = tile_off<BK>(64 * wn + l32, 2 * ks + h) + kTileK;
-    }
-    // kStages LDS stages: the copy of chunk kc + kStages - 1 is issued while chunk kc is multiplied
-    // (with one workgroup per CU nothing else hides the copies' latency: three stages there).
-    constexpr int kStages = NW == 8 ? 3 : 2, kAhead = kStages - 1;
-    constexpr int kCopiesPerFetch = (kTileK + kTileQ) / (1024 * NW);  // per wave
-    const int chunks = p.d / BK;
-    for (int c = 0; c < kAhead && c < chunks; ++c) fetch(c * BK, c);
-    wait_direct_loads();
-    __syncthreads();
-    auto chunk = [&](int kc, auto stage_off) {
-        const int so = stage_off;  // a compile-time constant in the unrolled two-stage loop
-        const bool more = kc + kAhead < chunks;
-        if (more) fetch((kc + kAhead) * BK, (kc + kAhead) % kStages);
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 a[2], q[2];
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                a[t] = FragOffsets<BK>::read(smem, rk[ks], so + 32 * t * (BK * 2));
-                q[t] = FragOffsets<BK>::read(smem, rq[ks], so + 32 * t * (BK * 2));
-            }
-#pragma unroll
-            for (int tm = 0; tm < 2; ++tm)
-#pragma unroll
-                for (int tn = 0; tn < 2; ++tn) s[tm][tn] = mfma32(a[tm], q[tn], s[tm][tn]);
-        }
-        // chunk kc + 1 must have landed; with three stages the copies just issued may stay in flight
-        if (more && kStages == 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopiesPerFetch) : "memory");
-        else wait_direct_loads();
-        __syncthreads();
-    };
-    if constexpr (kStages == 2) {
-        int kc = 0;
-        for (; kc + 2 <= chunks; kc += 2) {
-            chunk(kc, std::integral_constant<int, 0>{});
-            chunk(kc + 1, std::integral_constant<int, kStage>{});
-        }
-        if (kc < chunks) chunk(kc, std::integral_constant<int, 0>{});
-    } else {
-        for (int kc = 0; kc < chunks; ++kc) chunk(kc, (kc % kStages) * kStage);
-    }
-
-    // epilogue
-    const float c = p.scale * kLog2e;
-    const bool need_mask = (p.causal && k0 + kKeys - 1 > q0) || (k0 + kKeys > p.n);
-#pragma unroll
-    for (int tn = 0; tn < 2; ++tn) {
-        const int q = q0 + 64 * wn + 32 * tn + l32;
-        const bool q_ok = q < p.n;
-        if (MODE == kStats) {
-            float x[2][16];
-            float mx = -__builtin_inff();
-#pragma unroll
-            for (int tm = 0; tm < 2; ++tm)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    float v = s[tm][tn][i] * c;
-                    const int key = k0 + 64 * wm + 32 * tm + acc_row(i, h);
-                    if (need_mask && (key >= p.n || (p.causal && key > q))) v = -__builtin_inff();
-                    x[tm][i] = v;
-                    mx = fmaxf(mx, v);
-                }
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_use = mx == -__builtin_inff() ? 0.f : mx;
-            float sum = 0.f;
-#pragma unroll
-            for (int tm = 0; tm < 2; ++tm)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(x[tm][i] - m_use);
-            sum += __shfl_xor(sum, 32, 64);
-            if (q_ok && h == 0) {
-                const long o = ((long)bh * p.n + q) * (2 * nbq) + k0 / 64 + wm;
-                p.stat_m[o] = mx;
-                p.stat_l[o] = sum;
-            }
-        } else {
-            const float lse2 = q_ok ? p.LSEout[(long)bh * p.n + q] * kLog2e : __builtin_inff();
-            // The tile goes to LDS first ([query][key] rows in the stages the k-loop has left) and from there to
-            // memory in whole rows: written straight from the accumulators, every store would touch 32 rows with 16
-            // bytes each.
-            char* prow = smem + (64 * wn + 32 * tn + l32) * (kKeys * 2);
-#pragma unroll
-            for (int tm = 0; tm < 2; ++tm)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int key = k0 + 64 * wm + 32 * tm + 8 * g + 4 * h;
-                    // 16-byte chunk of this row that holds keys 64 wm + 32 tm + 8 g .. + 7 (swizzled), half h
-                    const int slot = (((8 * wm + 4 * tm + g) ^ swz<kKeys>(64 * wn + 32 * tn + l32)) << 4) + 8 * h;
-                    float pv[4];
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        float v = __builtin_amdgcn_exp2f(s[tm][tn][4 * g + r] * c - lse2);
-                        // a fully masked row has LSE = -inf: exp2(+inf) must not leak out
-                        if (lse2 == -__builtin_inff()) v = 0.f;
-                        if (need_mask && (key + r >= p.n || (p.causal && key + r > q))) v = 0.f;
-                        pv[r] = v;
-                    }
-                    u32x2 a;
-                    a[0] = pack_bf16(pv[0], pv[1]);
-                    a[1] = pack_bf16(pv[2], pv[3]);
-                    *reinterpret_cast<u32x2*>(prow + slot) = a;
-                }
-        }
-    }
-    if (MODE != kStats) {
-        __syncthreads();
-        constexpr int kChunks = kKeys / 8, kRowsPerPass = kThreadsHere / kChunks;  // 16 rows per pass
-        const int cc = tid % kChunks;
-#pragma unroll
-        for (int r0 = 0; r0 < 128; r0 += kRowsPerPass) {
-            const int row = r0 + tid / kChunks;
-            const long off = ((long)bh * p.npad + q0 + row) * p.npad + k0 + 8 * cc;
-            *reinterpret_cast<u32x4*>(p.P + off) = *reinterpret_cast<const u32x4*>(smem + tile_off<kKeys>(row, cc));
-        }
-    }
-}
-
-// Backward scores kernel: P and dS tiles of 128 queries x 256 keys.  The two products of a tile are formed one after the
-// other - S^T over all of d, then dP^T over all of d - so that a wave can hold a 128 x 64 block (4 x 2 accumulators) of
-// the one in progress: 256 x 128 tiles with four waves move 384 bytes from memory per MFMA instead of the 512 of
-// 128 x 128 tiles, a k-step needs the chunks of two operands only (24 KB), and three LDS stages (copies two steps ahead)
-// fit two workgroups on a CU.  Between the passes P stays in registers, rounded to bf16 as it is stored
-// (dS = P (dP - delta) is formed from that rounded P).  Accumulator: lane <-> query, register <-> key.
-constexpr int kScoreBwdStage = (256 + 128) * 32 * 2, kScoreLdsBwd2 = 3 * kScoreBwdStage;
-__global__ void __launch_bounds__(kThreads, 2) ld_scores_bwd_kernel(LargeDParams p) {
+// Scores kernel, tiles of 128 queries x 256 keys, four waves with a 128 x 64 block (4 x 2 accumulators) each; a
+// k-step needs 32-column chunks of two operands (24 KB), and three LDS stages (copies two steps ahead) fit two
+// workgroups on a CU.  Accumulator: lane <-> query, register <-> key.  Modes:
+//   kStats    row maximum and sum of exp of S per 64-key chunk (the forward's first sweep)
+//   kProbs    P = exp(S - LSE) written to the workspace (the forward's second sweep)
+//   kBackward P and dS.  The two products of a tile are formed one after the other - S^T over all of d, then dP^T
+//             over all of d - so that the wave can hold its block of the one in progress: 256 x 128 tiles move 384 bytes
+//             from memory per MFMA instead of the 512 of 128 x 128 tiles with both products at once.  Between the
+//             passes P stays in registers, rounded to bf16 as it is stored (dS = P (dP - delta) uses that rounded P).
+enum ScoreMode { kStats = 0, kProbs = 1, kBackward = 2 };
+constexpr int kScoreStage = (256 + 128) * 32 * 2, kScoreLds = 3 * kScoreStage;
+template <int MODE>
+__global__ void __launch_bounds__(kThreads, 2) ld_scores_kernel(LargeDParams p) {
     constexpr int BK = 32, kKeys = 256;
-    constexpr int kTileK = kKeys * BK * 2, kTileQ = 128 * BK * 2, kStage = kScoreBwdStage;
+    constexpr int kTileK = kKeys * BK * 2, kTileQ = 128 * BK * 2, kStage = kScoreStage;
     constexpr int kOutTile = 128 * kKeys * 2;  // a [128 queries][256 keys] bf16 tile staged for the stores
     static_assert(kOutTile <= 3 * kStage, "the staged tile reuses the stages");
     extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -354,16 +149,52 @@ __global__ void __launch_bounds__(kThreads, 2) ld_scores_bwd_kernel(LargeDParams
         __syncthreads();  // the stages are free again
     };
 
-    // ---- pass 1: S^T -> P (bf16, kept packed in registers and written out)
+    // ---- pass 1: S^T
     product(p.K + base, p.Q + base);
     const float cs = p.scale * kLog2e;
     const bool need_mask = (p.causal && k0 + kKeys - 1 > q0) || (k0 + kKeys > p.n);
-    uint32_t pk[4][2][8];
+    if constexpr (MODE == kStats) {
+#pragma unroll
+        for (int tn = 0; tn < 2; ++tn) {
+            const int q = q0 + 64 * wn + 32 * tn + l32;
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {  // the two 64-key chunks of this wave's 128 keys
+                float x[2][16];
+                float mx = -__builtin_inff();
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        float v = c[2 * half + t][tn][i] * cs;
+                        const int key = k0 + 128 * wm + 64 * half + 32 * t + acc_row(i, h);
+                        if (need_mask && (key >= p.n || (p.causal && key > q))) v = -__builtin_inff();
+                        x[t][i] = v;
+                        mx = fmaxf(mx, v);
+                    }
+                mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+                const float m_use = mx == -__builtin_inff() ? 0.f : mx;
+                float sum = 0.f;
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(x[t][i] - m_use);
+                sum += __shfl_xor(sum, 32, 64);
+                if (q < p.n && h == 0) {
+                    const long o = ((long)bh * p.n + q) * (2 * nbq) + k0 / 64 + 2 * wm + half;
+                    p.stat_m[o] = mx;
+                    p.stat_l[o] = sum;
+                }
+            }
+        }
+        return;
+    }
+    // P (bf16): written out and, in the backward, kept packed in registers
+    uint32_t pk[MODE == kBackward ? 4 : 1][2][8];
 #pragma unroll
     for (int tn = 0; tn < 2; ++tn) {
         const int q = q0 + 64 * wn + 32 * tn + l32;
         const bool q_ok = q < p.n;
-        const float lse2 = q_ok ? p.LSE[(long)bh * p.n + q] * kLog2e : __builtin_inff();
+        const float lse2 = q_ok ? (MODE == kBackward ? p.LSE : p.LSEout)[(long)bh * p.n + q] * kLog2e : __builtin_inff();
         char* prow = smem + (64 * wn + 32 * tn + l32) * (kKeys * 2);
 #pragma unroll
         for (int tm = 0; tm < 4; ++tm)
@@ -381,13 +212,16 @@ __global__ void __launch_bounds__(kThreads, 2) ld_scores_bwd_kernel(LargeDParams
                 u32x2 a;
                 a[0] = pack_bf16(pv[0], pv[1]);
                 a[1] = pack_bf16(pv[2], pv[3]);
-                pk[tm][tn][2 * g] = a[0];
-                pk[tm][tn][2 * g + 1] = a[1];
+                if constexpr (MODE == kBackward) {
+                    pk[tm][tn][2 * g] = a[0];
+                    pk[tm][tn][2 * g + 1] = a[1];
+                }
                 const int slot = (((16 * wm + 4 * tm + g) ^ swz<kKeys>(64 * wn + 32 * tn + l32)) << 4) + 8 * h;
                 *reinterpret_cast<u32x2*>(prow + slot) = a;
             }
     }
     store_tile(p.P);
+    if constexpr (MODE != kBackward) return;
 
     // ---- pass 2: dP^T -> dS = P (dP - delta)
     product(p.V + base, p.dO + base);
@@ -604,12 +438,11 @@ static void run_gemm(const LargeDParams& p, const __bf16* A, const __bf16* B, __
     hipLaunchKernelGGL(ld_gemm_kernel<A_KMAJOR>, grid, dim3(kThreads), kGemmLds, stream, p, g);
 }
 
-constexpr int kScoreLdsFwd = 3 * (256 + 128) * 32 * 2;      // 8 waves: three stages of a K and a Q chunk
 // LDS sizes of the large-d kernels on the current device (set on every call: cheap, and per device).
 hipError_t configure_larged() {
-    hipError_t e = set_lds(reinterpret_cast<const void*>(ld_scores_kernel<kStats, 8>), kScoreLdsFwd);
-    if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_scores_kernel<kProbs, 8>), kScoreLdsFwd);
-    if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_scores_bwd_kernel), kScoreLdsBwd2);
+    hipError_t e = set_lds(reinterpret_cast<const void*>(ld_scores_kernel<kStats>), kScoreLds);
+    if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_scores_kernel<kProbs>), kScoreLds);
+    if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_scores_kernel<kBackward>), kScoreLds);
     if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_gemm_kernel<true>), kGemmLds);
     if (e == hipSuccess) e = set_lds(reinterpret_cast<const void*>(ld_gemm_kernel<false>), kGemmLds);
     return e;
@@ -620,16 +453,16 @@ hipError_t launch_larged(bool backward, const LargeDParams& p, hipStream_t strea
     if (ce != hipSuccess) return ce;
     const unsigned bh = (unsigned)(p.batch * p.heads);
     const unsigned nbq = (unsigned)(p.npad / 128);
-    const dim3 fgrid(nbq * (unsigned)(p.npad / 256) * bh), fblock(512);  // forward modes: 256-key tiles, 8 waves
+    const dim3 sgrid(nbq * (unsigned)(p.npad / 256) * bh);  // score tiles: 128 queries x 256 keys
     const dim3 block(kThreads);
     if (!backward) {
-        hipLaunchKernelGGL((ld_scores_kernel<kStats, 8>), fgrid, fblock, kScoreLdsFwd, stream, p);
+        hipLaunchKernelGGL(ld_scores_kernel<kStats>, sgrid, block, kScoreLds, stream, p);
         const long rows = (long)bh * p.n;
         hipLaunchKernelGGL(ld_lse_combine_kernel, dim3((unsigned)((rows + kThreads - 1) / kThreads)), block, 0, stream, p);
-        hipLaunchKernelGGL((ld_scores_kernel<kProbs, 8>), fgrid, fblock, kScoreLdsFwd, stream, p);
+        hipLaunchKernelGGL(ld_scores_kernel<kProbs>, sgrid, block, kScoreLds, stream, p);
         run_gemm<false>(p, p.P, p.V, p.Oout, 1.f, stream);
     } else {
-        hipLaunchKernelGGL(ld_scores_bwd_kernel, dim3(nbq * (unsigned)(p.npad / 256) * bh), block, kScoreLdsBwd2, stream, p);
+        hipLaunchKernelGGL(ld_scores_kernel<kBackward>, sgrid, block, kScoreLds, stream, p);
         run_gemm<true>(p, p.P, p.dO, p.dV, 1.f, stream);
         run_gemm<true>(p, p.dS, p.Q, p.dK, p.scale, stream);
         run_gemm<false>(p, p.dS, p.K, p.dQ, p.scale, stream);

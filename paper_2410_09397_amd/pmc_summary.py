@@ -20,7 +20,7 @@ import os
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 COPY_BYTES = float(1 << 30)  # bytes read, and bytes written, by the calibration copy
-BWD_KERNELS = ("delta_kernel", "bwd_dkdv", "bwd_dq", "ld_scores_bwd_kernel", "ld_gemm_kernel", "generic_delta",
+BWD_KERNELS = ("delta_kernel", "bwd_dkdv", "bwd_dq", "ld_scores_kernel<2>", "ld_scores_kernel<(attn::ScoreMode)2>", "ld_gemm_kernel", "generic_delta",
                "generic_dq", "generic_dkdv", "block_len_kernel", "block_order_kernel", "block_order_fused_kernel", "bwd_prep_kernel",
                "bwd_onepass_kernel", "bwd_splitd_kernel")
 
@@ -41,7 +41,8 @@ def source_hash():
 
 def traffic_key(workload, tiling):
     return workload if not tiling else "%s@tiling%d" % (workload, tiling)
-FWD_KERNELS = ("fwd_kernel", "ld_scores_kernel<0,", "ld_scores_kernel<1,", "ld_lse_combine", "generic_fwd")
+FWD_KERNELS = ("fwd_kernel", "ld_scores_kernel<0>", "ld_scores_kernel<1>", "ld_scores_kernel<(attn::ScoreMode)0>",
+               "ld_scores_kernel<(attn::ScoreMode)1>", "ld_lse_combine", "generic_fwd")
 
 
 def _one(pattern):
@@ -153,7 +154,7 @@ def main():
         rd = fetch.get(name, 0.0) * f_r * 1024.0
         wr = write.get(name, 0.0) * f_w * 1024.0
         # a kernel launched more than once per call (the large-d GEMM) counts that many times
-        wb, wf = per_call_weights(name, calls, base_calls, any("ld_scores_bwd_kernel" in n for n in stats))
+        wb, wf = per_call_weights(name, calls, base_calls, any("ld_scores_kernel<2>" in n or "ScoreMode)2>" in n for n in stats))
         for grp, k in (("bwd", wb), ("fwd", wf)):
             tot[grp][0] += avg * k
             tot[grp][1] += rd * k
