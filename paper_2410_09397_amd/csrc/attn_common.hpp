@@ -148,6 +148,23 @@ struct FragOffsets {
         i16x8 r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
         return __builtin_bit_cast(bf16x8, r);
     }
+    // The transposed fetch with the k index in natural order: element t of lane half h <-> row row16 + 8h + t, which
+    // pairs with an operand that is read row-major as whole 16-byte chunks.  tr_natural(lane, mt, half) is the
+    // address register (half 1 = rows + 4: one step of the row swizzle, 16 bytes), read_t_natural the fetch.
+    static __device__ __forceinline__ int tr_natural(int lane, int mt, int half) {
+        const int s = lane & 15;
+        const int col = 16 * ((lane >> 4) & 1) + 4 * (s & 3);
+        const int base = tile_off<D>(8 * (lane >> 5) + (s >> 2), col >> 3) + ((col & 4) << 1);
+        return base ^ (mt << 6) ^ (half << 4);
+    }
+    static __device__ __forceinline__ bf16x8 read_t_natural(const char* lds, int tr_lo, int tr_hi, int row16, int imm = 0) {
+        i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 ATTN_LDS*)(lds + tr_lo + (imm + row16 * (D * 2))));
+        i16x4 hi =
+            __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 ATTN_LDS*)(lds + tr_hi + (imm + (row16 + 4) * (D * 2))));
+        typedef short i16x8 __attribute__((ext_vector_type(8)));
+        i16x8 r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(bf16x8, r);
+    }
 };
 
 // The address registers of all fragments of a [rows x D] tile (static indices only).

@@ -38,7 +38,7 @@ struct LargeDParams {
     float* LSEout;      // forward output
     const float* delta; // backward: rowsum(dO o O)
     __bf16 *P, *dS;
-    float *stat_m, *stat_l;  // forward: per 64-key chunk row maximum and sum, [bh][n][npad / 64]
+    float *stat_m, *stat_l;  // forward: per 64-key chunk row maximum and sum, [bh][npad / 64][n]
     long stride_b, stride_h, stride_n;
     int batch, heads, n, d, npad;
     float scale;

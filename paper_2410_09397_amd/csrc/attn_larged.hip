@@ -180,7 +180,7 @@ __global__ void __launch_bounds__(kThreads, 2) ld_scores_kernel(LargeDParams p) 
                     for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(x[t][i] - m_use);
                 sum += __shfl_xor(sum, 32, 64);
                 if (q < p.n && h == 0) {
-                    const long o = ((long)bh * p.n + q) * (2 * nbq) + k0 / 64 + 2 * wm + half;
+                    const long o = ((long)bh * (2 * nbq) + k0 / 64 + 2 * wm + half) * p.n + q;  // [bh][chunk][query]
                     p.stat_m[o] = mx;
                     p.stat_l[o] = sum;
                 }
@@ -251,21 +251,43 @@ __global__ void __launch_bounds__(kThreads, 2) ld_scores_kernel(LargeDParams p) 
     store_tile(p.dS);
 }
 
-// LSE from the per-chunk statistics: one thread per row.
+// LSE from the per-chunk statistics.  A workgroup takes 16 rows; 16 threads per row each fold every 16th chunk into a
+// running (maximum, sum) pair, and the 16 pairs of a row are folded through LDS (one thread per row alone spent its time
+// waiting for one load after the other).  Statistics are [bh][chunk][query]: threads that stand for consecutive
+// queries read consecutive floats.
+constexpr int kCombineRows = 16, kCombineParts = kThreads / kCombineRows;
 __global__ void __launch_bounds__(kThreads) ld_lse_combine_kernel(LargeDParams p) {
-    const long r = (long)blockIdx.x * kThreads + threadIdx.x;
-    if (r >= (long)p.batch * p.heads * p.n) return;
-    const int q = (int)(r % p.n);
+    __shared__ float part_m[kCombineParts][kCombineRows], part_l[kCombineParts][kCombineRows];
+    const int rl = threadIdx.x % kCombineRows, g = threadIdx.x / kCombineRows;
+    const long rows = (long)p.batch * p.heads * p.n;
+    const long r = (long)blockIdx.x * kCombineRows + rl;
+    const bool ok = r < rows;
+    const int q = ok ? (int)(r % p.n) : 0;
     const int nb = p.npad / 128;
-    const int chunks = 2 * (p.causal ? q / 128 + 1 : nb);
-    const float* m = p.stat_m + r * (2 * nb);
-    const float* l = p.stat_l + r * (2 * nb);
-    float M = -__builtin_inff();
-    for (int c = 0; c < chunks; ++c) M = fmaxf(M, m[c]);
-    float L = 0.f;
-    if (M != -__builtin_inff())
-        for (int c = 0; c < chunks; ++c)
-            if (m[c] != -__builtin_inff()) L += l[c] * __builtin_amdgcn_exp2f(m[c] - M);
+    const int chunks = ok ? 2 * (p.causal ? q / 128 + 1 : nb) : 0;
+    const long pitch = p.n;
+    const long head = ok ? (r / p.n) * (2 * nb) * pitch + q : 0;
+    float M = -__builtin_inff(), L = 0.f;
+    for (int c = g; c < chunks; c += kCombineParts) {
+        const float mc = p.stat_m[head + c * pitch], lc = p.stat_l[head + c * pitch];
+        if (mc != -__builtin_inff()) {
+            const float top = fmaxf(M, mc);
+            L = L * __builtin_amdgcn_exp2f(M - top) + lc * __builtin_amdgcn_exp2f(mc - top);  // (exp2(-inf) = 0 at the start)
+            M = top;
+        }
+    }
+    part_m[g][rl] = M;
+    part_l[g][rl] = L;
+    __syncthreads();
+    if (g != 0 || !ok) return;
+    for (int k = 1; k < kCombineParts; ++k) {
+        const float mk = part_m[k][rl], lk = part_l[k][rl];
+        if (mk != -__builtin_inff()) {
+            const float top = fmaxf(M, mk);
+            L = L * __builtin_amdgcn_exp2f(M - top) + lk * __builtin_amdgcn_exp2f(mk - top);
+            M = top;
+        }
+    }
     p.LSEout[r] = L > 0.f ? (M + __builtin_amdgcn_logf(L)) * kLn2 : -__builtin_inff();
 }
 
@@ -339,9 +361,10 @@ __global__ void __launch_bounds__(kThreads, 2) ld_gemm_kernel(LargeDParams p, Ge
         else copy_a.load(gA + k + (long)m0 * p.npad, at);
         copy_b.load(gB + n0, p.stride_n, k, p.n, at + kTileA, tid);
     };
-    // A read transposed: one register pair per 32-row tile t.  A as stored: one register per
-    // 16-byte chunk of this lane's row (the 32-row tiles are immediates apart).
-    int ra[4][2], rc[4], rb[2][2];
+    // A read transposed: one register pair per 32-row tile t.  A as stored: one register per k-step, the 16-byte
+    // chunk 2 ks + h of this lane's row (the 32-row tiles are immediates apart); B is then fetched with its k index
+    // in the same natural order.  (Reading A in 8-byte halves to match the other order cost 44 % LDS bank conflicts.)
+    int ra[4][2], rc[BK / 16], rb[2][2];
     {
         FragOffsets<TM> fa;
         FragOffsets<128> fb;
@@ -351,12 +374,15 @@ __global__ void __launch_bounds__(kThreads, 2) ld_gemm_kernel(LargeDParams p, Ge
         for (int t = 0; t < 4; ++t) {
             ra[t][0] = fa.tr(4 * wm + t, 0);
             ra[t][1] = fa.tr(4 * wm + t, 1);
-            rc[t] = tile_off<BK>(128 * wm + l32, t) + 8 * h;
         }
+        // A as stored: whole 16-byte chunks of this lane's row (k in natural order), chunk 2 ks + h
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) rc[ks] = tile_off<BK>(128 * wm + l32, 2 * ks + h);
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int half = 0; half < 2; ++half) rb[t][half] = fb.tr(2 * wn + t, half) + kTileA;
+            for (int half = 0; half < 2; ++half)
+                rb[t][half] = (A_KMAJOR ? fb.tr(2 * wn + t, half) : FragOffsets<128>::tr_natural(lane, 2 * wn + t, half)) + kTileA;
     }
     // Three stages: the copies of step k + 2 are issued while step k is multiplied, so two steps' worth of bytes
     // (48 KB per workgroup) are in flight; with two stages the product kernels waited for memory at every step.
@@ -381,16 +407,13 @@ __global__ void __launch_bounds__(kThreads, 2) ld_gemm_kernel(LargeDParams p, Ge
                 if (A_KMAJOR) {
                     a[t] = FragOffsets<TM>::read_t(smem, ra[t][0], ra[t][1], 16 * ks, so);
                 } else {
-                    // k order of the transposed reads: 8-byte halves of chunks 2 ks and 2 ks + 1
-                    const int imm = so + 32 * t * (BK * 2);
-                    const u32x2 lo = *reinterpret_cast<const u32x2*>(smem + rc[2 * ks] + imm);
-                    const u32x2 hi = *reinterpret_cast<const u32x2*>(smem + rc[2 * ks + 1] + imm);
-                    const u32x4 r = {lo[0], lo[1], hi[0], hi[1]};
-                    a[t] = __builtin_bit_cast(bf16x8, r);
+                    a[t] = FragOffsets<BK>::read(smem, rc[ks], so + 32 * t * (BK * 2));
                 }
             }
 #pragma unroll
-            for (int t = 0; t < 2; ++t) b[t] = FragOffsets<128>::read_t(smem, rb[t][0], rb[t][1], 16 * ks, so);
+            for (int t = 0; t < 2; ++t)
+                b[t] = A_KMAJOR ? FragOffsets<128>::read_t(smem, rb[t][0], rb[t][1], 16 * ks, so)
+                                : FragOffsets<128>::read_t_natural(smem, rb[t][0], rb[t][1], 16 * ks, so);
 #pragma unroll
             for (int tm = 0; tm < 4; ++tm)
 #pragma unroll
@@ -458,7 +481,7 @@ hipError_t launch_larged(bool backward, const LargeDParams& p, hipStream_t strea
     if (!backward) {
         hipLaunchKernelGGL(ld_scores_kernel<kStats>, sgrid, block, kScoreLds, stream, p);
         const long rows = (long)bh * p.n;
-        hipLaunchKernelGGL(ld_lse_combine_kernel, dim3((unsigned)((rows + kThreads - 1) / kThreads)), block, 0, stream, p);
+        hipLaunchKernelGGL(ld_lse_combine_kernel, dim3((unsigned)((rows + kCombineRows - 1) / kCombineRows)), block, 0, stream, p);
         hipLaunchKernelGGL(ld_scores_kernel<kProbs>, sgrid, block, kScoreLds, stream, p);
         run_gemm<false>(p, p.P, p.V, p.Oout, 1.f, stream);
     } else {
